@@ -1,0 +1,145 @@
+"""Python face of the fp64 CPU oracle (oracle/scalekv_oracle.c).
+
+TEST INFRASTRUCTURE.  Only tests/, __graft_entry__.smoke() and bench.py's
+cpu_baseline leg may import this package.  It never imports the HIP binding and
+the HIP binding never imports it.
+
+All functions take numpy (or torch CPU) arrays of any float dtype, widen them
+to float64 and call the C routines, one (sequence, head) unit per leading
+index.  See the C file for what each step computes and which passage of the
+paper it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+from .build import build as _build
+
+_lib = None
+
+_c_dp = ctypes.POINTER(ctypes.c_double)
+_c_ip = ctypes.POINTER(ctypes.c_int32)
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build())
+        _lib.scalekv_oracle_num_threads.restype = ctypes.c_int
+        _lib.scalekv_oracle_cache_lengths.restype = ctypes.c_int
+        _lib.scalekv_oracle_select.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().scalekv_oracle_num_threads())
+
+
+def _f64(x) -> np.ndarray:
+    if hasattr(x, "detach"):  # torch tensor on the CPU
+        x = x.detach().to("cpu").double().numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _dp(a: Optional[np.ndarray]):
+    return a.ctypes.data_as(_c_dp) if a is not None else None
+
+
+def _ip(a: Optional[np.ndarray]):
+    return a.ctypes.data_as(_c_ip) if a is not None else None
+
+
+def default_scale(d: int) -> float:
+    return 1.0 / float(d) ** 0.5
+
+
+def score(qw, k, scale: Optional[float] = None, return_attention: bool = False):
+    """Eq. 5.  qw: [U, N, d] window queries, k: [U, len, d] cached keys.
+    Returns (s [U, len], log_s [U, len]) and, if asked, the attention rows
+    A [U, N, len]."""
+    qw, k = _f64(qw), _f64(k)
+    U, N, d = qw.shape
+    L = k.shape[1]
+    scale = default_scale(d) if scale is None else float(scale)
+    s = np.zeros((U, L)); ls = np.zeros((U, L))
+    a = np.zeros((U, N, L)) if return_attention else None
+    for u in range(U):
+        lib().scalekv_oracle_score(_dp(qw[u]), N, _dp(k[u]), L, d, ctypes.c_double(scale),
+                                   _dp(s[u]), _dp(ls[u]), _dp(a[u]) if a is not None else None)
+    return (s, ls, a) if return_attention else (s, ls)
+
+
+def select(scores, budget: int) -> np.ndarray:
+    """Top-min(budget, len) per unit, ties to the lower index, ascending.
+    scores: [U, len] -> idx [U, keep] int32."""
+    scores = _f64(scores)
+    U, L = scores.shape
+    keep = max(0, min(int(budget), L))
+    idx = np.zeros((U, keep), dtype=np.int32)
+    for u in range(U):
+        got = lib().scalekv_oracle_select(_dp(scores[u]), L, int(budget), _ip(idx[u]))
+        assert got == keep
+    return idx
+
+
+def compact(src, idx, cur) -> np.ndarray:
+    """dst = [src[idx] ; cur] per unit.  src [U, len, d], idx [U, keep],
+    cur [U, n_cur, d] -> [U, keep + n_cur, d] (float64 copies)."""
+    src, cur = _f64(src), _f64(cur)
+    idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    U, _, d = src.shape
+    keep, n_cur = idx.shape[1], cur.shape[1]
+    dst = np.zeros((U, keep + n_cur, d))
+    for u in range(U):
+        lib().scalekv_oracle_compact(_dp(src[u]), _ip(idx[u]), keep, _dp(cur[u]), n_cur, d, _dp(dst[u]))
+    return dst
+
+
+def attend(q, k, v, scale: Optional[float] = None) -> np.ndarray:
+    """Unmasked softmax attention per unit. q [U, n_q, d], k/v [U, kv, d]."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    U, n_q, d = q.shape
+    kv = k.shape[1]
+    scale = default_scale(d) if scale is None else float(scale)
+    out = np.zeros((U, n_q, d))
+    lib().scalekv_oracle_attend_batch(U, _dp(q), n_q, _dp(k), _dp(v), kv, d, ctypes.c_double(scale), _dp(out))
+    return out
+
+
+def step(q, k_cur, v_cur, win_idx: Sequence[int], k_src, v_src, budget: int,
+         scale: Optional[float] = None, force_idx=None):
+    """One (layer, scale) call: score -> select -> compact (+append) -> attend.
+    q/k_cur/v_cur [U, n_cur, d]; k_src/v_src [U, cache_len, d].
+    Returns dict(k_dst, v_dst [U, keep+n_cur, d], idx [U, keep], scores
+    [U, cache_len], out [U, n_cur, d], new_len)."""
+    q, k_cur, v_cur, k_src, v_src = map(_f64, (q, k_cur, v_cur, k_src, v_src))
+    U, n_cur, d = q.shape
+    L = k_src.shape[1]
+    scale = default_scale(d) if scale is None else float(scale)
+    win = np.ascontiguousarray(np.asarray(list(win_idx), dtype=np.int32))
+    keep = max(0, min(int(budget), L))
+    fidx = None
+    if force_idx is not None:
+        fidx = np.ascontiguousarray(np.asarray(force_idx, dtype=np.int32))
+        keep = fidx.shape[1]
+    k_dst = np.zeros((U, keep + n_cur, d)); v_dst = np.zeros((U, keep + n_cur, d))
+    idx = np.zeros((U, keep), dtype=np.int32)
+    sc = np.zeros((U, L)); out = np.zeros((U, n_cur, d))
+    lib().scalekv_oracle_step_batch(
+        U, _dp(q), _dp(k_cur), _dp(v_cur), n_cur, _ip(win), len(win), _dp(k_src), _dp(v_src), L,
+        int(budget), d, ctypes.c_double(scale), _ip(fidx), keep if fidx is not None else 0,
+        _dp(k_dst), _dp(v_dst), _ip(idx), _dp(sc), _dp(out))
+    return dict(k_dst=k_dst, v_dst=v_dst, idx=idx, scores=sc, out=out, new_len=keep + n_cur)
+
+
+def cache_lengths(prefix: int, n_tok: Sequence[int], budget: Sequence[int]) -> Tuple[np.ndarray, np.ndarray, int]:
+    """(len entering each scale, keep at each scale, final length)."""
+    n_tok = np.ascontiguousarray(np.asarray(n_tok, dtype=np.int32))
+    budget = np.ascontiguousarray(np.asarray(budget, dtype=np.int32))
+    K = len(n_tok)
+    li = np.zeros(K, dtype=np.int32); kp = np.zeros(K, dtype=np.int32)
+    final = lib().scalekv_oracle_cache_lengths(int(prefix), _ip(n_tok), _ip(budget), K, _ip(li), _ip(kp))
+    return li, kp, int(final)
