@@ -1,0 +1,149 @@
+/*
+ * scalekv.h -- C ABI of the ScaleKV per-scale, per-layer KV-cache step for
+ * AMD MI355X (gfx950).
+ *
+ * One call of scalekv_step does, for every (sequence, head) unit independently,
+ * what Sec. 3.3 ("KV Cache Selection") of the paper describes for one layer at
+ * one scale:
+ *   1. score    importance of every cached token = attention mass it receives
+ *               from the observation-window queries of the current token map
+ *               (Eq. 5);
+ *   2. select   the top-k cached tokens under the layer's budget (Sec. 3.3,
+ *               "select the top-k^l tokens"; budgets come from Eq. 4);
+ *   3. compact  keep the selected K/V rows, drop the rest, append the current
+ *               map's K/V (Sec. 3.3, last sentence of the selection paragraph);
+ *   4. attend   the current map's queries attend, unmasked, over the kept rows
+ *               plus the map's own K/V (Sec. 3.1: a scale's tokens are produced
+ *               in parallel, conditioned on earlier scales).
+ * The four stages are also exported on their own.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * Memory.  Every pointer is DEVICE memory unless its comment says "host".  All
+ *   buffers are allocated, owned and freed by the caller; the library holds no
+ *   device state and allocates nothing.  Device pointers must be 16-byte
+ *   aligned.
+ * Layout.  Dense tensors are row-major [n_seq, n_head, rows, head_dim] with no
+ *   padding.  A cache (scalekv_kv) is [n_seq, n_head, capacity, head_dim] with
+ *   explicit sequence and head strides (in elements) and a contiguous row of
+ *   head_dim elements; only the first `len` rows of each unit are meaningful.
+ *   Element type is shape->dtype (fp32 or bf16).  Scores are fp32, indices
+ *   int32.
+ * Asynchrony.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL
+ *   is the default stream).  No call synchronises with the host.  Integer
+ *   results returned through host pointers (keep, new length) are computed on
+ *   the host from the arguments and are valid on return.
+ * Errors.  Each call returns a scalekv_status.  Arguments are checked on the
+ *   host before anything is launched, so a failing call has no side effects.
+ *   scalekv_last_error() gives a message for the calling thread's last failure.
+ * Limits.  head_dim must be 64 or 128; n_win <= SCALEKV_MAX_WINDOW;
+ *   cache lengths and row counts are int32 and each (rows * head_dim) product
+ *   must fit int32.
+ */
+#ifndef SCALEKV_H
+#define SCALEKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SCALEKV_MAX_WINDOW 16
+
+typedef enum {
+  SCALEKV_OK = 0,
+  SCALEKV_ERR_INVALID_ARG = 1, /* null/misaligned pointer, negative size, length beyond capacity,
+                                  window index out of range, overlapping source and destination */
+  SCALEKV_ERR_UNSUPPORTED = 2, /* head_dim or dtype the kernels are not built for */
+  SCALEKV_ERR_WORKSPACE = 3,   /* ws == NULL or ws_bytes below scalekv_workspace_bytes() */
+  SCALEKV_ERR_HIP = 4          /* a kernel launch reported an error */
+} scalekv_status;
+
+typedef enum { SCALEKV_F32 = 0, SCALEKV_BF16 = 1 } scalekv_dtype;
+
+typedef struct {
+  int32_t n_seq;    /* sequences (batch rows; classifier-free-guidance rows count separately) */
+  int32_t n_head;   /* attention heads; K/V have the same head count as Q */
+  int32_t head_dim; /* 64 or 128 */
+  int32_t dtype;    /* scalekv_dtype of Q, K, V and the attention output */
+  float sm_scale;   /* multiplies q.k before the softmax; <= 0 means 1/sqrt(head_dim) (Eq. 5) */
+} scalekv_shape;
+
+typedef struct {
+  void* ptr;           /* device, [n_seq, n_head, capacity, head_dim] */
+  int64_t seq_stride;  /* elements between consecutive sequences */
+  int64_t head_stride; /* elements between consecutive heads; >= capacity * head_dim */
+  int32_t capacity;    /* rows available per (sequence, head) */
+} scalekv_kv;
+
+/* Bytes of device workspace that score/step need for caches up to max_cache_len
+ * rows and up to max_q current tokens.  *out is host memory. */
+scalekv_status scalekv_workspace_bytes(const scalekv_shape* shape, int32_t max_cache_len,
+                                       int32_t max_q, size_t* out);
+
+/* Eq. 5.  q_win [S,H,n_win,d]: the observation-window queries.  k: cache whose
+ * first cache_len rows are scored.  log_scores [S,H,cache_len] fp32 receives
+ * log s_i, where s_i = sum over window rows j of softmax_i(q_j.k_i*sm_scale);
+ * the softmax runs over exactly the cache_len rows given.  The logarithm is a
+ * monotone image of s_i that stays finite when exp() underflows in fp32, so the
+ * ranking of Sec. 3.3 is unchanged.  cache_len == 0 is a no-op.  n_win >= 1. */
+scalekv_status scalekv_score(const scalekv_shape* shape, const void* q_win, int32_t n_win,
+                             const scalekv_kv* k, int32_t cache_len, float* log_scores, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/* Top-k of Sec. 3.3 per (sequence, head): keep = min(budget, cache_len) indices
+ * of the largest scores, equal scores resolved towards the lower index, written
+ * in ascending index order to idx [S,H,keep].  *keep_out (host, may be NULL)
+ * receives keep.  budget == 0 or cache_len == 0 writes nothing. */
+scalekv_status scalekv_select(const scalekv_shape* shape, const float* scores, int32_t cache_len,
+                              int32_t budget, int32_t* idx, int32_t* keep_out, void* stream);
+
+/* Pruning of Sec. 3.3: for t < keep, dst row t = src row idx[t] (K and V with
+ * the same idx [S,H,keep]); then rows keep .. keep+n_cur-1 = the current map's
+ * k_cur / v_cur [S,H,n_cur,d].  idx == NULL means the identity (keep all of
+ * the first `keep` rows, keep <= cache_len).  k_cur/v_cur may be NULL iff
+ * n_cur == 0.  Copies are bit-exact.  Source and destination caches must not
+ * overlap.  Requires keep + n_cur <= dst capacity and idx entries in
+ * [0, cache_len) (entries are not checked on the device). */
+scalekv_status scalekv_compact(const scalekv_shape* shape, const scalekv_kv* k_src,
+                               const scalekv_kv* v_src, int32_t cache_len, const int32_t* idx,
+                               int32_t keep, const void* k_cur, const void* v_cur, int32_t n_cur,
+                               const scalekv_kv* k_dst, const scalekv_kv* v_dst, void* stream);
+
+/* Unmasked attention of Sec. 3.1 / 3.3: out[t] = sum_i softmax_i(q_t.k_i *
+ * sm_scale) v_i over the first kv_len rows of k and v.  q, out [S,H,n_q,d].
+ * fp32 accumulation; bf16 inputs round the probabilities to bf16 before the
+ * P.V product.  n_q == 0 is a no-op; kv_len must be >= 1 when n_q > 0. */
+scalekv_status scalekv_attend(const scalekv_shape* shape, const void* q, int32_t n_q,
+                              const scalekv_kv* k, const scalekv_kv* v, int32_t kv_len, void* out,
+                              void* stream);
+
+/* The whole step.  q, k_cur, v_cur [S,H,n_cur,d] are the current map's
+ * projections; win_idx (host, n_win entries in [0, n_cur)) names the
+ * observation-window rows of q.  k_src/v_src hold cache_len rows.  On return
+ * (stream order) k_dst/v_dst hold keep + n_cur rows (keep = min(budget,
+ * cache_len)), out [S,H,n_cur,d] holds the attention output and, if idx_out
+ * (device, [S,H,keep]) is not NULL, the selected indices.  *new_len_out (host,
+ * may be NULL) = keep + n_cur.  budget >= cache_len keeps everything and skips
+ * scoring (the result is exact attention over cache and current map);
+ * budget == 0 attends over the current map only.  n_cur >= 1. */
+scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const void* k_cur,
+                            const void* v_cur, int32_t n_cur, const int32_t* win_idx,
+                            int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
+                            int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
+                            const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
+                            int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Message for the calling thread's most recent non-OK status (static storage,
+ * never NULL). */
+const char* scalekv_last_error(void);
+
+/* Library version string, e.g. "scalekv 0.1 gfx950". */
+const char* scalekv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCALEKV_H */

@@ -1,0 +1,23 @@
+"""ScaleKV hot path for AMD MI355X: thin Python binding over libscalekv.so.
+
+Argument marshalling only -- every step of the path (score, select, compact,
+attend, and the fused step) runs in the HIP kernels behind the C ABI declared
+in include/scalekv.h.  PyTorch is used for device memory and streams, nothing
+else.  There is no CPU fallback: if the library cannot be loaded, importing
+the binding's functions raises.
+"""
+from .binding import (  # noqa: F401
+    ScaleKVError,
+    Shape,
+    lib,
+    lib_path,
+    version,
+    workspace_bytes,
+    score,
+    select,
+    compact,
+    attend,
+    step,
+    MAX_WINDOW,
+    EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,223 @@
+"""ctypes binding with the same names as the C entry points.
+
+Each function checks tensor dtype/device/contiguity (so that a pointer handed
+to C means what the header says), passes raw device pointers, sizes and the
+current HIP stream, and raises ScaleKVError on a non-OK status.  No arithmetic
+happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+MAX_WINDOW = 16
+
+EXPORTED_SYMBOLS = (
+    "scalekv_workspace_bytes", "scalekv_score", "scalekv_select", "scalekv_compact",
+    "scalekv_attend", "scalekv_step", "scalekv_last_error", "scalekv_version",
+)
+
+_STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE", 4: "HIP"}
+
+
+class ScaleKVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"scalekv status {status} ({_STATUS.get(status, '?')}): {message}")
+        self.status = status
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("n_seq", ctypes.c_int32), ("n_head", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("sm_scale", ctypes.c_float)]
+
+
+class _CKv(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("seq_stride", ctypes.c_int64),
+                ("head_stride", ctypes.c_int64), ("capacity", ctypes.c_int32)]
+
+
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+
+
+@dataclass(frozen=True)
+class Shape:
+    n_seq: int
+    n_head: int
+    head_dim: int
+    dtype: torch.dtype
+    sm_scale: float = 0.0   # <= 0: 1/sqrt(head_dim)
+
+    def c(self) -> _CShape:
+        if self.dtype not in _DTYPES:
+            raise ScaleKVError(2, f"dtype {self.dtype} is not float32 or bfloat16")
+        return _CShape(self.n_seq, self.n_head, self.head_dim, _DTYPES[self.dtype], float(self.sm_scale))
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libscalekv.so")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libscalekv.so (built in-tree by paper_2505_19602_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -m paper_2505_19602_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(path)
+        L.scalekv_last_error.restype = ctypes.c_char_p
+        L.scalekv_version.restype = ctypes.c_char_p
+        for name in EXPORTED_SYMBOLS[:6]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().scalekv_version().decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise ScaleKVError(status, lib().scalekv_last_error().decode())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dense(t: torch.Tensor, shape: Shape, rows: int, name: str, dtype=None) -> torch.Tensor:
+    want = (shape.n_seq, shape.n_head, rows, shape.head_dim)
+    if tuple(t.shape) != want:
+        raise ScaleKVError(1, f"{name} has shape {tuple(t.shape)}, expected {want}")
+    if t.dtype != (dtype or shape.dtype):
+        raise ScaleKVError(1, f"{name} has dtype {t.dtype}, expected {dtype or shape.dtype}")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ScaleKVError(1, f"{name} must be a contiguous device tensor")
+    return t
+
+
+def _kv(t: torch.Tensor, shape: Shape, name: str) -> _CKv:
+    """[S,H,capacity,d] tensor (a view with larger strides is fine as long as
+    rows are contiguous) -> scalekv_kv."""
+    if t.dim() != 4 or t.shape[0] != shape.n_seq or t.shape[1] != shape.n_head or t.shape[3] != shape.head_dim:
+        raise ScaleKVError(1, f"{name} has shape {tuple(t.shape)}, expected [S,H,capacity,d]")
+    if t.dtype != shape.dtype or not t.is_cuda:
+        raise ScaleKVError(1, f"{name} must be a device tensor of dtype {shape.dtype}")
+    if t.stride(3) != 1 or t.stride(2) != shape.head_dim:
+        raise ScaleKVError(1, f"{name}: rows must be contiguous (strides {t.stride()})")
+    return _CKv(t.data_ptr(), t.stride(0), t.stride(1), t.shape[2])
+
+
+def workspace_bytes(shape: Shape, max_cache_len: int, max_q: int) -> int:
+    out = ctypes.c_size_t(0)
+    cs = shape.c()
+    _check(lib().scalekv_workspace_bytes(ctypes.byref(cs), int(max_cache_len), int(max_q), ctypes.byref(out)))
+    return int(out.value)
+
+
+def _ws(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return ctypes.c_void_p(0), ctypes.c_size_t(0)
+    if not ws.is_cuda or not ws.is_contiguous():
+        raise ScaleKVError(1, "workspace must be a contiguous device tensor")
+    return ctypes.c_void_p(ws.data_ptr()), ctypes.c_size_t(ws.numel() * ws.element_size())
+
+
+def score(shape: Shape, q_win: torch.Tensor, k: torch.Tensor, cache_len: int,
+          log_scores: torch.Tensor, ws: torch.Tensor) -> None:
+    """scalekv_score: q_win [S,H,n_win,d], k cache [S,H,cap,d] -> log_scores [S,H,cache_len] fp32."""
+    n_win = q_win.shape[2]
+    _dense(q_win, shape, n_win, "q_win")
+    if tuple(log_scores.shape) != (shape.n_seq, shape.n_head, cache_len) or log_scores.dtype != torch.float32 \
+            or not log_scores.is_cuda or not log_scores.is_contiguous():
+        raise ScaleKVError(1, "log_scores must be a contiguous fp32 device tensor [S,H,cache_len]")
+    cs, ck = shape.c(), _kv(k, shape, "k")
+    wp, wb = _ws(ws)
+    _check(lib().scalekv_score(ctypes.byref(cs), _ptr(q_win), int(n_win), ctypes.byref(ck), int(cache_len),
+                               _ptr(log_scores), wp, wb, _stream()))
+
+
+def select(shape: Shape, scores: torch.Tensor, cache_len: int, budget: int, idx: torch.Tensor) -> int:
+    """scalekv_select: scores [S,H,cache_len] fp32 -> idx [S,H,keep] int32; returns keep."""
+    if scores.dtype != torch.float32 or not scores.is_cuda or not scores.is_contiguous() \
+            or tuple(scores.shape) != (shape.n_seq, shape.n_head, cache_len):
+        raise ScaleKVError(1, "scores must be a contiguous fp32 device tensor [S,H,cache_len]")
+    keep = max(0, min(int(budget), int(cache_len)))
+    if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous() \
+            or tuple(idx.shape) != (shape.n_seq, shape.n_head, keep):
+        raise ScaleKVError(1, f"idx must be a contiguous int32 device tensor [S,H,{keep}]")
+    cs = shape.c()
+    out = ctypes.c_int32(-1)
+    _check(lib().scalekv_select(ctypes.byref(cs), _ptr(scores), int(cache_len), int(budget), _ptr(idx),
+                                ctypes.byref(out), _stream()))
+    return int(out.value)
+
+
+def compact(shape: Shape, k_src: torch.Tensor, v_src: torch.Tensor, cache_len: int,
+            idx: Optional[torch.Tensor], keep: int, k_cur: Optional[torch.Tensor],
+            v_cur: Optional[torch.Tensor], k_dst: torch.Tensor, v_dst: torch.Tensor) -> int:
+    """scalekv_compact; returns keep + n_cur."""
+    n_cur = 0 if k_cur is None else k_cur.shape[2]
+    if k_cur is not None:
+        _dense(k_cur, shape, n_cur, "k_cur")
+        _dense(v_cur, shape, n_cur, "v_cur")
+    if idx is not None:
+        if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous() \
+                or tuple(idx.shape) != (shape.n_seq, shape.n_head, keep):
+            raise ScaleKVError(1, f"idx must be a contiguous int32 device tensor [S,H,{keep}]")
+    cs = shape.c()
+    a, b, c, d = _kv(k_src, shape, "k_src"), _kv(v_src, shape, "v_src"), _kv(k_dst, shape, "k_dst"), _kv(v_dst, shape, "v_dst")
+    _check(lib().scalekv_compact(ctypes.byref(cs), ctypes.byref(a), ctypes.byref(b), int(cache_len), _ptr(idx),
+                                 int(keep), _ptr(k_cur), _ptr(v_cur), int(n_cur), ctypes.byref(c),
+                                 ctypes.byref(d), _stream()))
+    return keep + n_cur
+
+
+def attend(shape: Shape, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, kv_len: int,
+           out: torch.Tensor) -> None:
+    """scalekv_attend: q [S,H,n_q,d], caches k/v (first kv_len rows) -> out [S,H,n_q,d]."""
+    n_q = q.shape[2]
+    _dense(q, shape, n_q, "q")
+    _dense(out, shape, n_q, "out")
+    cs, ck, cv = shape.c(), _kv(k, shape, "k"), _kv(v, shape, "v")
+    _check(lib().scalekv_attend(ctypes.byref(cs), _ptr(q), int(n_q), ctypes.byref(ck), ctypes.byref(cv),
+                                int(kv_len), _ptr(out), _stream()))
+
+
+def step(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor,
+         win_idx: Sequence[int], k_src: torch.Tensor, v_src: torch.Tensor, cache_len: int, budget: int,
+         k_dst: torch.Tensor, v_dst: torch.Tensor, out: torch.Tensor,
+         idx_out: Optional[torch.Tensor], ws: Optional[torch.Tensor]) -> int:
+    """scalekv_step; returns the new cache length keep + n_cur."""
+    n_cur = q.shape[2]
+    _dense(q, shape, n_cur, "q"); _dense(k_cur, shape, n_cur, "k_cur"); _dense(v_cur, shape, n_cur, "v_cur")
+    _dense(out, shape, n_cur, "out")
+    keep = max(0, min(int(budget), int(cache_len)))
+    if idx_out is not None:
+        if idx_out.dtype != torch.int32 or not idx_out.is_cuda or not idx_out.is_contiguous() \
+                or tuple(idx_out.shape) != (shape.n_seq, shape.n_head, keep):
+            raise ScaleKVError(1, f"idx_out must be a contiguous int32 device tensor [S,H,{keep}]")
+    win = (ctypes.c_int32 * max(1, len(win_idx)))(*[int(w) for w in win_idx])
+    cs = shape.c()
+    a, b, c, d = _kv(k_src, shape, "k_src"), _kv(v_src, shape, "v_src"), _kv(k_dst, shape, "k_dst"), _kv(v_dst, shape, "v_dst")
+    wp, wb = _ws(ws)
+    new_len = ctypes.c_int32(-1)
+    _check(lib().scalekv_step(ctypes.byref(cs), _ptr(q), _ptr(k_cur), _ptr(v_cur), int(n_cur), win,
+                              int(len(win_idx)), ctypes.byref(a), ctypes.byref(b), int(cache_len), int(budget),
+                              ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len), _ptr(out), _ptr(idx_out),
+                              wp, wb, _stream()))
+    return int(new_len.value)

@@ -1,0 +1,342 @@
+// C ABI of the ScaleKV step: host-side argument checks, workspace carving and
+// kernel sequencing.  Nothing here touches device memory or synchronises; every
+// kernel goes onto the caller's stream in order.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/scalekv.h"
+#include "common.h"
+
+using namespace scalekv;
+
+namespace {
+
+thread_local char g_err[256] = "no error";
+
+scalekv_status fail(scalekv_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+scalekv_status hip_fail(hipError_t e, const char* what) {
+  return fail(SCALEKV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int elem_bytes(const scalekv_shape* s) { return s->dtype == SCALEKV_F32 ? 4 : 2; }
+
+float resolve_scale(const scalekv_shape* s) {
+  return s->sm_scale > 0.f ? s->sm_scale : 1.0f / sqrtf((float)s->head_dim);
+}
+
+scalekv_status check_shape(const scalekv_shape* s) {
+  if (!s) return fail(SCALEKV_ERR_INVALID_ARG, "shape is NULL");
+  if (s->n_seq <= 0 || s->n_head <= 0)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_seq and n_head must be positive (got %d, %d)",
+                s->n_seq, s->n_head);
+  if ((long long)s->n_seq * s->n_head > 65535)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "n_seq * n_head = %lld exceeds 65535",
+                (long long)s->n_seq * s->n_head);
+  if (s->dtype != SCALEKV_F32 && s->dtype != SCALEKV_BF16)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "dtype %d is neither SCALEKV_F32 nor SCALEKV_BF16",
+                s->dtype);
+  if (s->head_dim != 64 && s->head_dim != 128)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "head_dim %d is not 64 or 128", s->head_dim);
+  if (!(s->sm_scale == s->sm_scale))
+    return fail(SCALEKV_ERR_INVALID_ARG, "sm_scale is NaN");
+  return SCALEKV_OK;
+}
+
+// rows * head_dim must fit int32 (kernels index a unit with 32-bit offsets in places)
+scalekv_status check_rows(const scalekv_shape* s, long long rows, const char* name) {
+  if (rows < 0) return fail(SCALEKV_ERR_INVALID_ARG, "%s is negative (%lld)", name, rows);
+  if (rows * s->head_dim > 0x7fffffffLL)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "%s = %lld rows is too large", name, rows);
+  return SCALEKV_OK;
+}
+
+scalekv_status check_kv(const scalekv_shape* s, const scalekv_kv* kv, int rows_needed,
+                        const char* name) {
+  if (!kv) return fail(SCALEKV_ERR_INVALID_ARG, "%s is NULL", name);
+  if (!kv->ptr) return fail(SCALEKV_ERR_INVALID_ARG, "%s.ptr is NULL", name);
+  if (!aligned16(kv->ptr)) return fail(SCALEKV_ERR_INVALID_ARG, "%s.ptr is not 16-byte aligned", name);
+  if (kv->capacity < 0) return fail(SCALEKV_ERR_INVALID_ARG, "%s.capacity is negative", name);
+  if (rows_needed > kv->capacity)
+    return fail(SCALEKV_ERR_INVALID_ARG, "%s: %d rows needed but capacity is %d", name,
+                rows_needed, kv->capacity);
+  const long long unit = (long long)kv->capacity * s->head_dim;
+  const int epv = 16 / elem_bytes(s);
+  if (kv->head_stride < unit || kv->head_stride % epv)
+    return fail(SCALEKV_ERR_INVALID_ARG,
+                "%s.head_stride %lld must be >= capacity*head_dim (%lld) and a multiple of %d",
+                name, (long long)kv->head_stride, unit, epv);
+  if (kv->seq_stride < kv->head_stride * s->n_head || kv->seq_stride % epv)
+    return fail(SCALEKV_ERR_INVALID_ARG,
+                "%s.seq_stride %lld must be >= n_head*head_stride and a multiple of %d", name,
+                (long long)kv->seq_stride, epv);
+  return SCALEKV_OK;
+}
+
+scalekv_status check_dense(const void* p, bool required, const char* name) {
+  if (!p) return required ? fail(SCALEKV_ERR_INVALID_ARG, "%s is NULL", name) : SCALEKV_OK;
+  if (!aligned16(p)) return fail(SCALEKV_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+  return SCALEKV_OK;
+}
+
+// byte range [lo, hi) spanned by a cache
+void kv_span(const scalekv_shape* s, const scalekv_kv* kv, uintptr_t* lo, uintptr_t* hi) {
+  const long long e = elem_bytes(s);
+  *lo = reinterpret_cast<uintptr_t>(kv->ptr);
+  *hi = *lo + (uintptr_t)(((long long)(s->n_seq - 1) * kv->seq_stride +
+                           (long long)(s->n_head - 1) * kv->head_stride +
+                           (long long)kv->capacity * s->head_dim) * e);
+}
+
+bool overlaps(const scalekv_shape* s, const scalekv_kv* a, const scalekv_kv* b) {
+  uintptr_t al, ah, bl, bh;
+  kv_span(s, a, &al, &ah);
+  kv_span(s, b, &bl, &bh);
+  return al < bh && bl < ah;
+}
+
+KvView view(const scalekv_kv* kv) { return KvView{kv->ptr, kv->seq_stride, kv->head_stride}; }
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t logits_off, partial_off, scores_off, idx_off, total;
+  int len_pad, n_chunk;
+};
+
+WsLayout ws_layout(const scalekv_shape* s, int cache_len) {
+  WsLayout w;
+  const size_t U = (size_t)s->n_seq * s->n_head;
+  const int len = cache_len > 0 ? cache_len : 1;
+  w.len_pad = round_up(len, kLogitPad);
+  w.n_chunk = (len + kScoreChunk - 1) / kScoreChunk;
+  size_t off = 0;
+  w.logits_off = off;  off += align256(U * kMaxWindow * w.len_pad * sizeof(float));
+  w.partial_off = off; off += align256(U * w.n_chunk * 2 * kMaxWindow * sizeof(float));
+  w.scores_off = off;  off += align256(U * w.len_pad * sizeof(float));
+  w.idx_off = off;     off += align256(U * w.len_pad * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+
+scalekv_status check_ws(const scalekv_shape* s, int cache_len, void* ws, size_t ws_bytes) {
+  const WsLayout w = ws_layout(s, cache_len);
+  if (!ws) return fail(SCALEKV_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", w.total);
+  if (!aligned16(ws)) return fail(SCALEKV_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+  if (ws_bytes < w.total)
+    return fail(SCALEKV_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, w.total);
+  return SCALEKV_OK;
+}
+
+ScoreWorkspace score_ws(const WsLayout& w, void* ws) {
+  ScoreWorkspace sw;
+  sw.logits = reinterpret_cast<float*>(static_cast<char*>(ws) + w.logits_off);
+  sw.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + w.partial_off);
+  sw.len_pad = w.len_pad;
+  sw.n_chunk = w.n_chunk;
+  return sw;
+}
+
+#define SCALEKV_TRY(expr)                       \
+  do {                                          \
+    scalekv_status _st = (expr);                \
+    if (_st != SCALEKV_OK) return _st;          \
+  } while (0)
+
+#define SCALEKV_HIP(expr, what)                 \
+  do {                                          \
+    hipError_t _e = (expr);                     \
+    if (_e != hipSuccess) return hip_fail(_e, what); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* scalekv_last_error(void) { return g_err; }
+
+const char* scalekv_version(void) { return "scalekv 0.1 gfx950"; }
+
+scalekv_status scalekv_workspace_bytes(const scalekv_shape* shape, int32_t max_cache_len,
+                                       int32_t max_q, size_t* out) {
+  SCALEKV_TRY(check_shape(shape));
+  if (!out) return fail(SCALEKV_ERR_INVALID_ARG, "out is NULL");
+  if (max_q < 0) return fail(SCALEKV_ERR_INVALID_ARG, "max_q is negative");
+  SCALEKV_TRY(check_rows(shape, max_cache_len, "max_cache_len"));
+  *out = ws_layout(shape, max_cache_len).total;
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_score(const scalekv_shape* shape, const void* q_win, int32_t n_win,
+                             const scalekv_kv* k, int32_t cache_len, float* log_scores, void* ws,
+                             size_t ws_bytes, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  if (n_win < 1 || n_win > SCALEKV_MAX_WINDOW)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_win %d is outside 1..%d", n_win, SCALEKV_MAX_WINDOW);
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  SCALEKV_TRY(check_dense(q_win, true, "q_win"));
+  SCALEKV_TRY(check_kv(shape, k, cache_len, "k"));
+  if (!log_scores) return fail(SCALEKV_ERR_INVALID_ARG, "log_scores is NULL");
+  SCALEKV_TRY(check_ws(shape, cache_len, ws, ws_bytes));
+  if (cache_len == 0) return SCALEKV_OK;
+  const WsLayout w = ws_layout(shape, cache_len);
+  const ScoreWorkspace sw = score_ws(w, ws);
+  WindowRows rows;
+  for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? j : 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q_win,
+                                  (long long)n_win * shape->head_dim, rows, n_win, view(k),
+                                  cache_len, resolve_scale(shape), sw, st),
+              "score logits launch");
+  SCALEKV_HIP(launch_score_finalize(shape->n_seq * shape->n_head, n_win, cache_len, sw, log_scores,
+                                    cache_len, st),
+              "score finalize launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_select(const scalekv_shape* shape, const float* scores, int32_t cache_len,
+                              int32_t budget, int32_t* idx, int32_t* keep_out, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  if (budget < 0) return fail(SCALEKV_ERR_INVALID_ARG, "budget is negative (%d)", budget);
+  const int keep = budget < cache_len ? budget : cache_len;
+  if (keep > 0) {
+    if (!scores) return fail(SCALEKV_ERR_INVALID_ARG, "scores is NULL");
+    if (!idx) return fail(SCALEKV_ERR_INVALID_ARG, "idx is NULL");
+  }
+  if (keep_out) *keep_out = keep;
+  SCALEKV_HIP(launch_select(shape->n_seq * shape->n_head, scores, cache_len, cache_len, keep, idx,
+                            static_cast<hipStream_t>(stream)),
+              "select launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_compact(const scalekv_shape* shape, const scalekv_kv* k_src,
+                               const scalekv_kv* v_src, int32_t cache_len, const int32_t* idx,
+                               int32_t keep, const void* k_cur, const void* v_cur, int32_t n_cur,
+                               const scalekv_kv* k_dst, const scalekv_kv* v_dst, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  if (keep < 0 || keep > cache_len)
+    return fail(SCALEKV_ERR_INVALID_ARG, "keep %d is outside 0..cache_len (%d)", keep, cache_len);
+  if (n_cur < 0) return fail(SCALEKV_ERR_INVALID_ARG, "n_cur is negative (%d)", n_cur);
+  SCALEKV_TRY(check_rows(shape, (long long)keep + n_cur, "keep + n_cur"));
+  SCALEKV_TRY(check_kv(shape, k_src, cache_len, "k_src"));
+  SCALEKV_TRY(check_kv(shape, v_src, cache_len, "v_src"));
+  SCALEKV_TRY(check_kv(shape, k_dst, keep + n_cur, "k_dst"));
+  SCALEKV_TRY(check_kv(shape, v_dst, keep + n_cur, "v_dst"));
+  SCALEKV_TRY(check_dense(k_cur, n_cur > 0, "k_cur"));
+  SCALEKV_TRY(check_dense(v_cur, n_cur > 0, "v_cur"));
+  if (overlaps(shape, k_src, k_dst) || overlaps(shape, k_src, v_dst) ||
+      overlaps(shape, v_src, k_dst) || overlaps(shape, v_src, v_dst) ||
+      overlaps(shape, k_dst, v_dst))
+    return fail(SCALEKV_ERR_INVALID_ARG, "source and destination caches overlap");
+  SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
+                             view(k_src), view(v_src), idx, keep, k_cur, v_cur, n_cur, view(k_dst),
+                             view(v_dst), static_cast<hipStream_t>(stream)),
+              "compact launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_attend(const scalekv_shape* shape, const void* q, int32_t n_q,
+                              const scalekv_kv* k, const scalekv_kv* v, int32_t kv_len, void* out,
+                              void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  SCALEKV_TRY(check_rows(shape, n_q, "n_q"));
+  SCALEKV_TRY(check_rows(shape, kv_len, "kv_len"));
+  if (n_q == 0) return SCALEKV_OK;
+  if (kv_len < 1) return fail(SCALEKV_ERR_INVALID_ARG, "kv_len must be >= 1 when n_q > 0");
+  SCALEKV_TRY(check_dense(q, true, "q"));
+  SCALEKV_TRY(check_dense(out, true, "out"));
+  SCALEKV_TRY(check_kv(shape, k, kv_len, "k"));
+  SCALEKV_TRY(check_kv(shape, v, kv_len, "v"));
+  SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_q,
+                            view(k), view(v), kv_len, resolve_scale(shape), out,
+                            static_cast<hipStream_t>(stream)),
+              "attend launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const void* k_cur,
+                            const void* v_cur, int32_t n_cur, const int32_t* win_idx,
+                            int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
+                            int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
+                            const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
+                            int32_t* idx_out, void* ws, size_t ws_bytes, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  if (n_cur < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_cur must be >= 1 (got %d)", n_cur);
+  SCALEKV_TRY(check_rows(shape, n_cur, "n_cur"));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  if (budget < 0) return fail(SCALEKV_ERR_INVALID_ARG, "budget is negative (%d)", budget);
+  const int keep = budget < cache_len ? budget : cache_len;
+  const bool ranks = keep > 0 && keep < cache_len;  // otherwise nothing to choose
+  if (ranks) {
+    if (n_win < 1 || n_win > SCALEKV_MAX_WINDOW)
+      return fail(SCALEKV_ERR_INVALID_ARG, "n_win %d is outside 1..%d", n_win, SCALEKV_MAX_WINDOW);
+    if (n_win > n_cur)
+      return fail(SCALEKV_ERR_INVALID_ARG, "n_win %d exceeds n_cur %d", n_win, n_cur);
+    if (!win_idx) return fail(SCALEKV_ERR_INVALID_ARG, "win_idx is NULL");
+    for (int j = 0; j < n_win; ++j)
+      if (win_idx[j] < 0 || win_idx[j] >= n_cur)
+        return fail(SCALEKV_ERR_INVALID_ARG, "win_idx[%d] = %d is outside 0..n_cur-1", j,
+                    win_idx[j]);
+    SCALEKV_TRY(check_ws(shape, cache_len, ws, ws_bytes));
+  }
+  SCALEKV_TRY(check_rows(shape, (long long)keep + n_cur, "keep + n_cur"));
+  SCALEKV_TRY(check_dense(q, true, "q"));
+  SCALEKV_TRY(check_dense(k_cur, true, "k_cur"));
+  SCALEKV_TRY(check_dense(v_cur, true, "v_cur"));
+  SCALEKV_TRY(check_dense(out, true, "out"));
+  SCALEKV_TRY(check_kv(shape, k_src, cache_len, "k_src"));
+  SCALEKV_TRY(check_kv(shape, v_src, cache_len, "v_src"));
+  SCALEKV_TRY(check_kv(shape, k_dst, keep + n_cur, "k_dst"));
+  SCALEKV_TRY(check_kv(shape, v_dst, keep + n_cur, "v_dst"));
+  if (overlaps(shape, k_src, k_dst) || overlaps(shape, k_src, v_dst) ||
+      overlaps(shape, v_src, k_dst) || overlaps(shape, v_src, v_dst) ||
+      overlaps(shape, k_dst, v_dst))
+    return fail(SCALEKV_ERR_INVALID_ARG, "source and destination caches overlap");
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int U = shape->n_seq * shape->n_head;
+  const int32_t* idx = nullptr;  // identity unless a ranking is needed
+  if (ranks) {
+    const WsLayout w = ws_layout(shape, cache_len);
+    const ScoreWorkspace sw = score_ws(w, ws);
+    float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + w.scores_off);
+    int32_t* idx_ws = idx_out ? idx_out
+                              : reinterpret_cast<int32_t*>(static_cast<char*>(ws) + w.idx_off);
+    WindowRows rows;
+    for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
+    SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
+                                    (long long)n_cur * shape->head_dim, rows, n_win, view(k_src),
+                                    cache_len, resolve_scale(shape), sw, st),
+                "score logits launch");
+    SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
+                "score finalize launch");
+    SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, st), "select launch");
+    idx = idx_ws;
+  } else if (idx_out && keep > 0) {
+    // keep == cache_len: the selection is the identity
+    SCALEKV_HIP(launch_select(U, nullptr, 0, cache_len, keep, idx_out, st), "select launch");
+  }
+  SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
+                             view(k_src), view(v_src), idx, keep, k_cur, v_cur, n_cur, view(k_dst),
+                             view(v_dst), st),
+              "compact launch");
+  SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_cur,
+                            view(k_dst), view(v_dst), keep + n_cur, resolve_scale(shape), out, st),
+              "attend launch");
+  if (new_len_out) *new_len_out = keep + n_cur;
+  return SCALEKV_OK;
+}
+
+}  // extern "C"

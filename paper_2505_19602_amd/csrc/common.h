@@ -1,0 +1,83 @@
+// Internal declarations shared by the ScaleKV HIP translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace scalekv {
+
+constexpr int kMaxWindow = 16;     // window rows held per unit by the score kernels
+constexpr int kScoreChunk = 256;   // cached keys handled per workgroup in the score kernels
+constexpr int kLogitPad = 64;      // logits row stride is the cache length rounded up to this
+
+// A cache viewed by kernels: base pointer plus strides in elements.
+struct KvView {
+  const void* ptr;
+  long long seq_stride;
+  long long head_stride;
+};
+
+struct WindowRows {
+  int row[kMaxWindow];
+};
+
+struct ScoreWorkspace {
+  float* logits;    // [U][kMaxWindow][len_pad]
+  float* partial;   // [U][n_chunk][2][kMaxWindow]  (row max, row sum of exp(logit - max))
+  int len_pad;
+  int n_chunk;
+};
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// ---- launchers (each enqueues on `stream` and returns hipGetLastError()) ----
+
+hipError_t launch_score_logits(int dtype, int n_seq, int n_head, int d, const void* q,
+                               long long q_unit_stride, WindowRows rows, int n_win, KvView k,
+                               int cache_len, float sm_scale, ScoreWorkspace ws,
+                               hipStream_t stream);
+hipError_t launch_score_finalize(int n_unit, int n_win, int cache_len, ScoreWorkspace ws,
+                                 float* log_scores, long long score_unit_stride,
+                                 hipStream_t stream);
+hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
+                         int cache_len, int keep, int32_t* idx, hipStream_t stream);
+hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src, KvView v_src,
+                          const int32_t* idx, int keep, const void* k_cur, const void* v_cur,
+                          int n_cur, KvView k_dst, KvView v_dst, hipStream_t stream);
+hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q, int n_q, KvView k,
+                         KvView v, int kv_len, float sm_scale, void* out, hipStream_t stream);
+
+// ---- device helpers ----
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int kPerVec = 4;  // elements per 16-byte vector
+  __device__ static void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+};
+struct bf16_t { uint16_t bits; };
+template <>
+struct Elem<bf16_t> {
+  static constexpr int kPerVec = 8;
+  __device__ static void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+};
+
+// round-to-nearest-even float -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+}  // namespace scalekv

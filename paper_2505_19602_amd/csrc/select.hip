@@ -1,0 +1,146 @@
+// Top-k of Sec. 3.3 for one (sequence, head) unit per workgroup.
+//
+// Scores are mapped to order-preserving unsigned keys; a 4-pass, 8-bit radix
+// select finds the key T of the keep-th largest score; one stable pass then
+// emits, in ascending index order, every index with key > T and the first
+// (keep - #greater) indices with key == T.  Only integer compares are involved,
+// so the result is deterministic and ties always go to the lower index.
+#include "common.h"
+
+namespace scalekv {
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
+constexpr int kLdsKeys = 12288;  // units up to this many scores keep their keys in LDS
+
+__device__ __forceinline__ uint32_t order_key(float f) {
+  const uint32_t b = __float_as_uint(f + 0.0f);  // -0 and +0 rank equal
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+template <bool IN_LDS>
+__global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
+                                                          long long score_unit_stride,
+                                                          int cache_len, int keep,
+                                                          int32_t* __restrict__ idx) {
+  __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sel_bin, sel_remaining;
+  __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
+
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float* s = scores + unit * score_unit_stride;
+  auto key_at = [&](int i) -> uint32_t {
+    if constexpr (IN_LDS) return keys[i];
+    else return order_key(s[i]);
+  };
+  if constexpr (IN_LDS) {
+    for (int i = tid; i < cache_len; i += kThreads) keys[i] = order_key(s[i]);
+  }
+
+  // ---- radix select: T = key of the keep-th largest ----
+  uint32_t prefix = 0, mask = 0, remaining = keep;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < cache_len; i += kThreads) {
+      const uint32_t kk = key_at(i);
+      if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lane L owns bins 4L..4L+3; `above` = count in all bins higher than the lane's.
+      const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2],
+                     h3 = hist[4 * tid + 3];
+      const uint32_t mine = h0 + h1 + h2 + h3;
+      uint32_t incl = mine;  // inclusive suffix sum over lanes >= tid
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t other = __shfl_down(incl, off);
+        if (tid + off < 64) incl += other;
+      }
+      uint32_t above = incl - mine;
+      // walk the lane's bins from the top
+      const uint32_t hh[4] = {h3, h2, h1, h0};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        if (above < remaining && remaining <= above + hh[b]) {
+          sel_bin = 4 * tid + (3 - b);
+          sel_remaining = remaining - above;
+        }
+        above += hh[b];
+      }
+    }
+    __syncthreads();
+    prefix |= sel_bin << shift;
+    mask |= 255u << shift;
+    remaining = sel_remaining;
+    __syncthreads();
+  }
+  const uint32_t T = prefix;
+  const uint32_t need_eq = remaining;  // how many keys equal to T are taken (>= 1)
+
+  // ---- stable emission ----
+  const int per = (cache_len + kThreads - 1) / kThreads;
+  const int lo = min(tid * per, cache_len), hi = min(lo + per, cache_len);
+  uint32_t n_gt = 0, n_eq = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t kk = key_at(i);
+    n_gt += kk > T;
+    n_eq += kk == T;
+  }
+  // exclusive block scan of (n_gt, n_eq)
+  const int lane = tid & 63, wave = tid >> 6;
+  uint32_t sg = n_gt, se = n_eq;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t og = __shfl_up(sg, off), oe = __shfl_up(se, off);
+    if (lane >= off) { sg += og; se += oe; }
+  }
+  if (lane == 63) { wave_gt[wave] = sg; wave_eq[wave] = se; }
+  __syncthreads();
+  uint32_t base_g = 0, base_e = 0;
+  for (int w = 0; w < wave; ++w) { base_g += wave_gt[w]; base_e += wave_eq[w]; }
+  const uint32_t ex_g = base_g + sg - n_gt, ex_e = base_e + se - n_eq;
+  uint32_t pos = ex_g + min(ex_e, need_eq);
+  uint32_t eq_seen = ex_e;
+  int32_t* out = idx + (long long)unit * keep;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t kk = key_at(i);
+    if (kk > T) {
+      out[pos++] = i;
+    } else if (kk == T) {
+      if (eq_seen < need_eq) out[pos++] = i;
+      ++eq_seen;
+    }
+  }
+}
+
+__global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total) {
+  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < total) idx[e] = (int32_t)(e % keep);
+}
+
+}  // namespace
+
+hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
+                         int cache_len, int keep, int32_t* idx, hipStream_t stream) {
+  if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
+  if (keep >= cache_len) {  // keep everything: identity, no ranking needed
+    const long long total = (long long)n_unit * keep;
+    hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       idx, keep, total);
+    return hipGetLastError();
+  }
+  if (cache_len <= kLdsKeys)
+    hipLaunchKernelGGL(select_kernel<true>, dim3(n_unit), dim3(kThreads), 0, stream, scores,
+                       score_unit_stride, cache_len, keep, idx);
+  else
+    hipLaunchKernelGGL(select_kernel<false>, dim3(n_unit), dim3(kThreads), 0, stream, scores,
+                       score_unit_stride, cache_len, keep, idx);
+  return hipGetLastError();
+}
+
+}  // namespace scalekv

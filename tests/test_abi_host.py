@@ -1,0 +1,154 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device (so these
+run without a GPU; pointers below are fake but aligned and never dereferenced)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2505_19602_amd as skv
+from paper_2505_19602_amd import binding as B
+from paper_2505_19602_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(skv.lib_path()):
+        hip_build.build(force=True)
+    return skv.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "scalekv.h")).read()
+    declared = set(re.findall(r"\b(scalekv_[a-z_]+)\s*\(", header))
+    assert declared == set(skv.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert "gfx950" in skv.version()
+
+
+def _shape(**kw):
+    base = dict(n_seq=1, n_head=2, head_dim=128, dtype=1, sm_scale=0.0)
+    base.update(kw)
+    return B._CShape(base["n_seq"], base["n_head"], base["head_dim"], base["dtype"], base["sm_scale"])
+
+
+def _kv(ptr=0x10000, cap=64, d=128, heads=2):
+    return B._CKv(ptr, cap * d * heads, cap * d, cap)
+
+
+def _err(L):
+    return L.scalekv_last_error().decode()
+
+
+def test_workspace_bytes_and_shape_errors(L):
+    out = ctypes.c_size_t(0)
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape()), 1000, 64, ctypes.byref(out)) == 0
+    small = out.value
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape()), 4000, 64, ctypes.byref(out)) == 0
+    assert out.value > small > 0
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape(head_dim=96)), 10, 1, ctypes.byref(out)) == 2
+    assert "head_dim" in _err(L)
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape(dtype=7)), 10, 1, ctypes.byref(out)) == 2
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape(n_seq=0)), 10, 1, ctypes.byref(out)) == 1
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape()), -1, 1, ctypes.byref(out)) == 1
+    assert L.scalekv_workspace_bytes(None, 10, 1, ctypes.byref(out)) == 1
+    assert L.scalekv_workspace_bytes(ctypes.byref(_shape()), 10, 1, None) == 1
+
+
+def test_score_argument_errors(L):
+    s, k = _shape(), _kv()
+    p = ctypes.c_void_p
+    big = ctypes.c_size_t(1 << 30)
+    assert L.scalekv_score(ctypes.byref(s), p(0x2000), 17, ctypes.byref(k), 10, p(0x3000), p(0x4000), big, None) == 1
+    assert L.scalekv_score(ctypes.byref(s), p(0x2000), 0, ctypes.byref(k), 10, p(0x3000), p(0x4000), big, None) == 1
+    assert L.scalekv_score(ctypes.byref(s), p(0), 4, ctypes.byref(k), 10, p(0x3000), p(0x4000), big, None) == 1
+    assert L.scalekv_score(ctypes.byref(s), p(0x2004), 4, ctypes.byref(k), 10, p(0x3000), p(0x4000), big, None) == 1
+    assert "aligned" in _err(L)
+    assert L.scalekv_score(ctypes.byref(s), p(0x2000), 4, ctypes.byref(k), 65, p(0x3000), p(0x4000), big, None) == 1
+    assert "capacity" in _err(L)
+    assert L.scalekv_score(ctypes.byref(s), p(0x2000), 4, ctypes.byref(k), 10, p(0x3000), p(0), big, None) == 3
+    assert L.scalekv_score(ctypes.byref(s), p(0x2000), 4, ctypes.byref(k), 10, p(0x3000), p(0x4000),
+                           ctypes.c_size_t(16), None) == 3
+    assert "needed" in _err(L)
+
+
+def test_select_argument_errors(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    keep = ctypes.c_int32(-5)
+    assert L.scalekv_select(ctypes.byref(s), p(0x1000), 10, -1, p(0x2000), ctypes.byref(keep), None) == 1
+    assert L.scalekv_select(ctypes.byref(s), p(0), 10, 3, p(0x2000), ctypes.byref(keep), None) == 1
+    assert L.scalekv_select(ctypes.byref(s), p(0x1000), 10, 3, p(0), ctypes.byref(keep), None) == 1
+    # budget 0 / empty cache: legal no-ops that need no device
+    assert L.scalekv_select(ctypes.byref(s), p(0), 10, 0, p(0), ctypes.byref(keep), None) == 0
+    assert keep.value == 0
+    assert L.scalekv_select(ctypes.byref(s), p(0), 0, 5, p(0), ctypes.byref(keep), None) == 0
+    assert keep.value == 0
+
+
+def test_compact_argument_errors(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    span = 64 * 128 * 2 * 2  # bytes of one fake cache
+    ks, vs = _kv(0x100000), _kv(0x100000 + span)
+    kd, vd = _kv(0x100000 + 2 * span), _kv(0x100000 + 3 * span)
+    ok_args = lambda: (ctypes.byref(s), ctypes.byref(ks), ctypes.byref(vs), 40, p(0x9000), 10, p(0xA000), p(0xB000), 20,
+                       ctypes.byref(kd), ctypes.byref(vd), None)
+    a = list(ok_args()); a[5] = 41      # keep > cache_len
+    assert L.scalekv_compact(*a) == 1
+    a = list(ok_args()); a[5] = -1
+    assert L.scalekv_compact(*a) == 1
+    a = list(ok_args()); a[8] = 60      # keep + n_cur > capacity
+    assert L.scalekv_compact(*a) == 1
+    a = list(ok_args()); a[6] = p(0)    # k_cur NULL with n_cur > 0
+    assert L.scalekv_compact(*a) == 1
+    a = list(ok_args()); a[9] = ctypes.byref(ks)  # dst aliases src
+    assert L.scalekv_compact(*a) == 1
+    assert "overlap" in _err(L)
+    a = list(ok_args()); a[10] = ctypes.byref(kd)  # v_dst aliases k_dst
+    assert L.scalekv_compact(*a) == 1
+    bad = B._CKv(0x100000, 10, 64 * 128, 64)   # seq stride smaller than one head
+    a = list(ok_args()); a[1] = ctypes.byref(bad)
+    assert L.scalekv_compact(*a) == 1
+
+
+def test_attend_and_step_argument_errors(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    span = 64 * 128 * 2 * 2
+    k, v = _kv(0x100000), _kv(0x100000 + span)
+    kd, vd = _kv(0x100000 + 2 * span), _kv(0x100000 + 3 * span)
+    assert L.scalekv_attend(ctypes.byref(s), p(0x1000), 8, ctypes.byref(k), ctypes.byref(v), 0, p(0x2000), None) == 1
+    assert L.scalekv_attend(ctypes.byref(s), p(0x1000), 8, ctypes.byref(k), ctypes.byref(v), 65, p(0x2000), None) == 1
+    assert L.scalekv_attend(ctypes.byref(s), p(0x1000), -1, ctypes.byref(k), ctypes.byref(v), 10, p(0x2000), None) == 1
+    assert L.scalekv_attend(ctypes.byref(s), p(0x1000), 0, ctypes.byref(k), ctypes.byref(v), 10, p(0x2000), None) == 0
+    win = (ctypes.c_int32 * 4)(0, 1, 2, 9)
+    new_len = ctypes.c_int32(0)
+    big = ctypes.c_size_t(1 << 30)
+
+    def step(n_cur=8, n_win=4, cache_len=40, budget=10, ws=p(0x8000), ws_bytes=big, w=win):
+        return L.scalekv_step(ctypes.byref(s), p(0x1000), p(0x2000), p(0x3000), n_cur, w, n_win, ctypes.byref(k),
+                              ctypes.byref(v), cache_len, budget, ctypes.byref(kd), ctypes.byref(vd),
+                              ctypes.byref(new_len), p(0x4000), p(0), ws, ws_bytes, None)
+    assert step() == 1 and "win_idx[3]" in _err(L)          # 9 >= n_cur
+    assert step(n_cur=0) == 1
+    assert step(n_win=17, n_cur=32) == 1
+    assert step(n_cur=16, budget=-2) == 1
+    assert step(n_cur=16, ws=p(0)) == 3
+    assert step(n_cur=16, ws_bytes=ctypes.c_size_t(8)) == 3
+    assert step(n_cur=16, cache_len=65) == 1
+    assert step(n_cur=60, budget=10) == 1 and "capacity" in _err(L)   # keep + n_cur > dst capacity
+
+
+def test_binding_rejects_wrong_tensors_before_calling_c():
+    shape = skv.Shape(1, 2, 128, torch.bfloat16)
+    q = torch.zeros(1, 2, 4, 128, dtype=torch.bfloat16)
+    with pytest.raises(skv.ScaleKVError):
+        skv.attend(shape, q, q, q, 4, q)          # CPU tensors are not device memory
+    with pytest.raises(skv.ScaleKVError):
+        skv.Shape(1, 2, 128, torch.float16).c()

@@ -1,0 +1,332 @@
+"""GPU parity: every stage and the whole step, through the C ABI, element by
+element against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_19602_amd as skv
+import workloads as W
+from parity_util import TOL, check_indices, check_output, units
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _rand(key, shape, dtype, scale=1.0):
+    return (W.normal_tensor(W.stream_key(1234, key), shape) * scale).to(dtype)
+
+
+def _note(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------- compact --
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("d", [64, 128])
+def test_compact_is_bit_exact_and_stays_in_bounds(dtype, d):
+    S, H, L, keep, n_cur, cap_src, cap_dst = 2, 3, 300, 77, 45, 320, 130
+    _note(f"compact dtype={dtype} d={d}")
+    shape = skv.Shape(S, H, d, dtype)
+    ks, vs = _rand(1, (S, H, cap_src, d), dtype), _rand(2, (S, H, cap_src, d), dtype)
+    kc, vc = _rand(3, (S, H, n_cur, d), dtype), _rand(4, (S, H, n_cur, d), dtype)
+    gen = torch.Generator().manual_seed(5)
+    idx = torch.stack([torch.sort(torch.randperm(L, generator=gen)[:keep])[0] for _ in range(S * H)])
+    idx = idx.reshape(S, H, keep).to(torch.int32)
+    canary = 7.0
+    kd = torch.full((S, H, cap_dst, d), canary, dtype=dtype, device=DEV); vd = torch.full_like(kd, canary)
+    new_len = skv.compact(shape, ks.to(DEV), vs.to(DEV), L, idx.to(DEV), keep, kc.to(DEV), vc.to(DEV), kd, vd)
+    torch.cuda.synchronize()
+    assert new_len == keep + n_cur
+    for src, cur, dst in ((ks, kc, kd), (vs, vc, vd)):
+        ref = oracle.compact(units(src)[:, :L].double(), idx.reshape(S * H, keep).numpy(), units(cur).double())
+        got = units(dst).double().numpy()
+        assert np.array_equal(got[:, :new_len], ref)
+        assert np.all(got[:, new_len:] == canary)          # rows past the new length untouched
+
+
+def test_compact_identity_strided_and_empty_parts():
+    S, H, d, L, n_cur = 1, 4, 128, 50, 9
+    dtype = torch.bfloat16
+    shape = skv.Shape(S, H, d, dtype)
+    # caches that are views into larger allocations (head stride > capacity * d)
+    big_src = _rand(10, (S, H, 2, 64, d), dtype).to(DEV)
+    ks, vs = big_src[:, :, 0], big_src[:, :, 1]
+    big_dst = torch.zeros(S, H, 2, 80, d, dtype=dtype, device=DEV)
+    kd, vd = big_dst[:, :, 0], big_dst[:, :, 1]
+    kc, vc = _rand(11, (S, H, n_cur, d), dtype).to(DEV), _rand(12, (S, H, n_cur, d), dtype).to(DEV)
+    assert skv.compact(shape, ks, vs, L, None, L, kc, vc, kd, vd) == L + n_cur     # idx NULL = identity
+    torch.cuda.synchronize()
+    assert torch.equal(kd[:, :, :L], ks[:, :, :L]) and torch.equal(vd[:, :, L:L + n_cur], vc)
+    assert torch.equal(kd[:, :, L:L + n_cur], kc) and torch.equal(vd[:, :, :L], vs[:, :, :L])
+    # nothing kept, nothing appended: legal no-ops
+    assert skv.compact(shape, ks, vs, L, None, 0, kc, vc, kd, vd) == n_cur
+    assert skv.compact(shape, ks, vs, L, None, 5, None, None, kd, vd) == 5
+    assert skv.compact(shape, ks, vs, 0, None, 0, None, None, kd, vd) == 0
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ score --
+
+@pytest.mark.parametrize("dtype,d,L,n_win", [
+    (torch.bfloat16, 128, 1000, 16), (torch.bfloat16, 128, 257, 5), (torch.bfloat16, 128, 1, 16),
+    (torch.bfloat16, 64, 700, 16), (torch.float32, 64, 333, 8), (torch.float32, 128, 64, 1),
+    (torch.bfloat16, 128, 6489, 16),
+])
+def test_score_matches_oracle(dtype, d, L, n_win):
+    S, H = 2, 2
+    _note(f"score dtype={dtype} d={d} L={L} n_win={n_win}")
+    shape = skv.Shape(S, H, d, dtype)
+    qw = _rand(20, (S, H, n_win, d), dtype, 1.5)
+    k = _rand(21, (S, H, L + 3, d), dtype, 1.5)
+    ls = torch.full((S, H, L), float("nan"), device=DEV)
+    ws = torch.empty(skv.workspace_bytes(shape, L, 16), dtype=torch.uint8, device=DEV)
+    skv.score(shape, qw.to(DEV), k.to(DEV), L, ls, ws)
+    torch.cuda.synchronize()
+    s_ref, ls_ref = oracle.score(units(qw), units(k)[:, :L])
+    got = ls.cpu().numpy().reshape(S * H, L).astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - ls_ref).max() < 2e-4
+    np.testing.assert_allclose(np.exp(got).sum(-1), n_win, rtol=1e-4)   # Eq. 5: scores total N
+
+
+def test_score_survives_fp32_underflow():
+    # peaked logits: most probabilities underflow in fp32, their logs must not
+    S, H, d, L, n_win = 1, 2, 128, 500, 16
+    shape = skv.Shape(S, H, d, torch.bfloat16)
+    qw = _rand(22, (S, H, n_win, d), torch.bfloat16, 6.0)
+    k = _rand(23, (S, H, L, d), torch.bfloat16, 6.0)
+    ls = torch.empty(S, H, L, device=DEV)
+    ws = torch.empty(skv.workspace_bytes(shape, L, 16), dtype=torch.uint8, device=DEV)
+    skv.score(shape, qw.to(DEV), k.to(DEV), L, ls, ws)
+    torch.cuda.synchronize()
+    s_ref, ls_ref = oracle.score(units(qw), units(k))
+    assert ls_ref.min() < -100                      # exp() of this is 0 in fp32
+    got = ls.cpu().numpy().reshape(S * H, L).astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - ls_ref).max() < 2e-3        # logits up to ~400: 1e-6 relative each
+
+
+# ----------------------------------------------------------------- select --
+
+@pytest.mark.parametrize("L,budget,kind", [
+    (1000, 100, "normal"), (1000, 1, "normal"), (1000, 999, "normal"), (6489, 1622, "normal"),
+    (777, 300, "ties"), (64, 10, "equal"), (5, 3, "ties"), (13000, 650, "normal"), (13000, 12999, "ties"),
+    (300, 300, "normal"), (300, 1000, "normal"),
+])
+def test_select_is_bit_exact_on_given_scores(L, budget, kind):
+    S, H = 2, 3
+    _note(f"select L={L} budget={budget} kind={kind}")
+    shape = skv.Shape(S, H, 128, torch.bfloat16)
+    x = W.normal_tensor(W.stream_key(99, L, budget), (S, H, L))
+    if kind == "ties":
+        x = torch.round(x * 2) / 2            # a handful of distinct values, signed zeros included
+        x[0, 0, ::7] = -0.0
+    elif kind == "equal":
+        x = torch.full_like(x, -3.25)
+    keep = min(budget, L)
+    idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+    assert skv.select(shape, x.to(DEV), L, budget, idx) == keep
+    torch.cuda.synchronize()
+    ref = oracle.select(x.reshape(S * H, L).double().numpy(), budget)   # same fp32 values, widened
+    assert np.array_equal(idx.cpu().numpy().reshape(S * H, keep), ref)
+
+
+# ----------------------------------------------------------------- attend --
+
+@pytest.mark.parametrize("dtype,d,n_q,kv_len", [
+    (torch.bfloat16, 128, 300, 700), (torch.bfloat16, 128, 1, 64), (torch.bfloat16, 128, 129, 65),
+    (torch.bfloat16, 128, 128, 1), (torch.bfloat16, 128, 257, 1000), (torch.bfloat16, 64, 200, 333),
+    (torch.float32, 64, 70, 150), (torch.float32, 128, 33, 95), (torch.float32, 64, 1, 1),
+])
+def test_attend_matches_oracle(dtype, d, n_q, kv_len):
+    S, H = 2, 2
+    _note(f"attend dtype={dtype} d={d} n_q={n_q} kv_len={kv_len}")
+    shape = skv.Shape(S, H, d, dtype)
+    q = _rand(30, (S, H, n_q, d), dtype, 1.3)
+    k = _rand(31, (S, H, kv_len + 5, d), dtype, 1.3)
+    v = _rand(32, (S, H, kv_len + 5, d), dtype)
+    # rows past kv_len must be ignored even if they hold garbage
+    k[:, :, kv_len:] = float("nan"); v[:, :, kv_len:] = float("nan")
+    out = torch.full((S, H, n_q, d), float("nan"), dtype=dtype, device=DEV)
+    skv.attend(shape, q.to(DEV), k.to(DEV), v.to(DEV), kv_len, out)
+    torch.cuda.synchronize()
+    ref = oracle.attend(units(q), units(k)[:, :kv_len], units(v)[:, :kv_len])
+    mx, mean = check_output(out, ref, dtype, "attend")
+    _note(f"  max {mx:.2e} mean {mean:.2e}")
+
+
+def test_attend_closed_forms_on_gpu():
+    S, H, d, n_q, kv = 1, 2, 128, 140, 260
+    dtype = torch.bfloat16
+    shape = skv.Shape(S, H, d, dtype)
+    q = _rand(33, (S, H, n_q, d), dtype).to(DEV)
+    k = _rand(34, (S, H, kv, d), dtype).to(DEV)
+    row = _rand(35, (S, H, 1, d), dtype).to(DEV)
+    out = torch.empty(S, H, n_q, d, dtype=dtype, device=DEV)
+    skv.attend(shape, q, k, row.expand(S, H, kv, d).contiguous(), kv, out)      # all V rows equal -> O = v
+    torch.cuda.synchronize()
+    assert (out.float() - row.float()).abs().max() < 2e-2
+    v = _rand(36, (S, H, kv, d), dtype).to(DEV)
+    skv.attend(shape, torch.zeros_like(q), k, v, kv, out)                       # Q = 0 -> mean of V
+    torch.cuda.synchronize()
+    assert (out.float() - v.float().mean(2, keepdim=True)).abs().max() < 2e-2
+
+
+# ------------------------------------------------------------------- step --
+
+def _run_chain(cfg, layers, unit_ids, check_all_units):
+    """Run all scales of `cfg` for the given layers on the GPU through
+    scalekv_step and follow each (layer, unit) with the oracle."""
+    dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    S, H, d = cfg.n_seq, cfg.n_head, cfg.head_dim
+    shape = skv.Shape(S, H, d, dtype)
+    cap = W.dst_capacity(cfg)
+    table = W.budget_table(cfg)
+    ws = torch.empty(skv.workspace_bytes(shape, cap, max(cfg.n_tokens(k) for k in range(1, cfg.n_scale + 1))),
+                     dtype=torch.uint8, device=DEV)
+    stats = dict(exact=0, band=0, max_err=0.0)
+    for layer in layers:
+        kp, vp = W.make_prefix(cfg, layer, DEV)
+        bufs = [(torch.zeros(S, H, cap, d, dtype=dtype, device=DEV), torch.zeros(S, H, cap, d, dtype=dtype, device=DEV))
+                for _ in range(2)]
+        src_k, src_v, cache_len = kp, vp, cfg.prefix
+        u_sel = list(range(S * H)) if check_all_units else unit_ids
+        ref_k = units(kp)[u_sel].double().numpy(); ref_v = units(vp)[u_sel].double().numpy()
+        for k in range(1, cfg.n_scale + 1):
+            _note(f"step cfg={cfg.name} layer={layer} scale={k} cache_len={cache_len}")
+            x = W.make_step_inputs(cfg, layer, k, DEV)
+            n_cur, budget = cfg.n_tokens(k), table[layer][k - 1]
+            win = W.window_indices(cfg, n_cur)
+            keep = min(budget, cache_len)
+            dst_k, dst_v = bufs[k % 2]
+            out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+            idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+            new_len = skv.step(shape, x.q, x.k_cur, x.v_cur, win, src_k, src_v, cache_len, budget,
+                               dst_k, dst_v, out, idx, ws)
+            torch.cuda.synchronize()
+            assert new_len == keep + n_cur
+            g_idx = idx.cpu().numpy().reshape(S * H, keep)[u_sel]
+            q_u, kc_u, vc_u = (units(t)[u_sel] for t in (x.q, x.k_cur, x.v_cur))
+            own = oracle.step(q_u, kc_u, vc_u, win, ref_k, ref_v, budget)
+            for i in range(len(u_sel)):
+                stats[check_indices(g_idx[i], own["scores"][i], keep, own["idx"][i])] += 1
+            # follow the GPU's (validated) choice so later scales stay comparable
+            ref = oracle.step(q_u, kc_u, vc_u, win, ref_k, ref_v, budget, force_idx=g_idx)
+            assert np.array_equal(units(dst_k)[u_sel, :new_len].double().numpy(), ref["k_dst"])   # bit-exact rows
+            assert np.array_equal(units(dst_v)[u_sel, :new_len].double().numpy(), ref["v_dst"])
+            mx, _ = check_output(units(out)[u_sel], ref["out"], dtype, f"step l{layer} k{k}")
+            stats["max_err"] = max(stats["max_err"], mx)
+            ref_k, ref_v = ref["k_dst"], ref["v_dst"]
+            src_k, src_v, cache_len = dst_k, dst_v, new_len
+    return stats
+
+
+def test_step_chain_tiny_fp32_all_units():
+    cfg = W.get_config("tiny")
+    stats = _run_chain(cfg, range(cfg.n_layer), None, True)
+    _note(f"tiny: {stats}")
+    assert stats["exact"] + stats["band"] == cfg.n_layer * cfg.n_scale * cfg.n_seq * cfg.n_head
+
+
+def test_step_chain_2b_512_sampled_units():
+    cfg = W.get_config("2b_512")
+    stats = _run_chain(cfg, [0, 17], [0, 5, 15], False)
+    _note(f"2b_512: {stats}")
+    assert stats["exact"] > 0
+
+
+def test_step_edge_budgets():
+    dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 90, 40
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = (_rand(40 + i, (S, H, n_cur, d), dtype) for i in range(3))
+    ks, vs = _rand(43, (S, H, L, d), dtype), _rand(44, (S, H, L, d), dtype)
+    ws = torch.empty(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    win = list(range(n_cur - 16, n_cur))
+    for budget in (0, 1, L - 1, L, L + 50):
+        keep = min(budget, L)
+        kd = torch.zeros(S, H, L + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+        out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+        # budget >= L and budget == 0 need no ranking, hence no workspace and no window
+        use_ws = ws if 0 < budget < L else None
+        new_len = skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), win if use_ws is not None else [],
+                           ks.to(DEV), vs.to(DEV), L, budget, kd, vd, out, idx, use_ws)
+        torch.cuda.synchronize()
+        assert new_len == keep + n_cur
+        ref = oracle.step(units(q), units(kc), units(vc), win, units(ks), units(vs), budget,
+                          force_idx=idx.cpu().numpy().reshape(S * H, keep))
+        if budget >= L:   # exact attention over the whole cache and the current map
+            full = oracle.attend(units(q), torch.cat([units(ks), units(kc)], 1), torch.cat([units(vs), units(vc)], 1))
+            assert np.abs(full - ref["out"]).max() < 1e-12
+            assert np.array_equal(idx.cpu().numpy().reshape(S * H, keep), np.tile(np.arange(L), (S * H, 1)))
+        check_output(out, ref["out"], dtype, f"budget {budget}")
+        own = oracle.step(units(q), units(kc), units(vc), win, units(ks), units(vs), budget)
+        for u in range(S * H):
+            check_indices(idx.cpu().numpy().reshape(S * H, keep)[u], own["scores"][u], keep, own["idx"][u])
+
+
+def test_step_one_hot_pattern_selects_its_argmax():
+    dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 400, 32
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = (_rand(50 + i, (S, H, n_cur, d), dtype, 0.1) for i in range(3))
+    ks, vs = _rand(53, (S, H, L, d), dtype, 0.1), _rand(54, (S, H, L, d), dtype)
+    direction = torch.nn.functional.normalize(W.normal_tensor(W.stream_key(55, 0), (d,)), dim=0)
+    win = [3, 10, 31]
+    q[:, :, win] = (5.0 * direction).to(dtype)
+    ks[:, 0, 123] = (40.0 * direction).to(dtype); ks[:, 1, 377] = (40.0 * direction).to(dtype)
+    ws = torch.empty(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    for budget in (1, 7):
+        kd = torch.zeros(S, H, budget + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+        out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+        idx = torch.zeros(S, H, budget, dtype=torch.int32, device=DEV)
+        skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), win, ks.to(DEV), vs.to(DEV), L, budget, kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        got = idx.cpu().numpy()
+        assert 123 in got[0, 0] and 377 in got[0, 1]
+
+
+# ------------------------------------------- full-size, bench launch shapes --
+
+def test_final_scale_full_size_sampled_against_oracle():
+    """The 64x64 scale at the bench's shape (16 sequences x 16 heads, 4096
+    queries, 6489 cached rows), all four budgets; the oracle checks sampled
+    units and, within them, sampled query rows."""
+    cfg = W.get_config("final_scale")
+    dtype = torch.bfloat16
+    S, H, d = cfg.n_seq, cfg.n_head, cfg.head_dim
+    shape = skv.Shape(S, H, d, dtype)
+    case = W.make_final_scale_case(cfg, DEV)
+    n_cur, L = case.q.shape[2], case.k_hist.shape[2]
+    assert (n_cur, L) == (4096, 6489)
+    win = W.window_indices(cfg, n_cur)
+    ws = torch.empty(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    sample_units = [0, 101, 255]
+    sample_rows = [0, 1, 777, 2048, 4095]
+    out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+    for budget in W.final_scale_budgets(cfg):
+        _note(f"final scale budget={budget}")
+        keep = min(budget, L)
+        kd = torch.zeros(S, H, keep + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+        new_len = skv.step(shape, case.q, case.k_cur, case.v_cur, win, case.k_hist, case.v_hist, L, budget,
+                           kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        assert new_len == keep + n_cur
+        g_idx = idx.cpu().numpy().reshape(S * H, keep)
+        assert np.all(np.diff(g_idx, axis=1) > 0) and g_idx.min() >= 0 and g_idx.max() < L   # all units: valid lists
+        boosted = case.boosted.cpu().numpy().reshape(S * H, L)
+        for u in sample_units:
+            qu, khu = units(case.q)[u:u + 1], units(case.k_hist)[u:u + 1]
+            s_ref, _ = oracle.score(qu[:, win], khu)
+            o_idx = oracle.select(s_ref, budget)
+            check_indices(g_idx[u], s_ref[0], keep, o_idx[0])
+            if budget < L and keep >= boosted[u].sum():
+                assert np.all(np.isin(np.nonzero(boosted[u])[0], g_idx[u]))      # the dominant keys are kept
+            k_new = oracle.compact(khu, g_idx[u:u + 1], units(case.k_cur)[u:u + 1])
+            v_new = oracle.compact(units(case.v_hist)[u:u + 1], g_idx[u:u + 1], units(case.v_cur)[u:u + 1])
+            assert np.array_equal(units(kd)[u, :new_len].double().numpy(), k_new[0])
+            assert np.array_equal(units(vd)[u, :new_len].double().numpy(), v_new[0])
+            ref = oracle.attend(qu[:, sample_rows], k_new, v_new)
+            check_output(units(out)[u:u + 1, sample_rows], ref, dtype, f"final scale u{u} b{budget}")
