@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""ScaleKV hot-path benchmark on one MI355X.
+
+One "step" = the whole multi-scale sequence of one image batch: for each of the
+13 scales and each of the 32 layers, one scalekv_step call (score -> select ->
+compact -> attend) over seeded synthetic Q/K/V of the Infinity-2B shape at
+1024^2, batch 8 with classifier-free-guidance rows (16 sequences).  All inputs
+and caches are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: the headline metric (ms per 13-scale image batch), the
+roofline of the dominant kernel (the bf16 MFMA attention) from HIP events
+recorded on the launch stream inside the timed region, per-stage times and
+bandwidths, and the fp64 CPU oracle timed on a bounded sample of the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """Raw hipEvent_t handles from the same HIP runtime the library uses."""
+
+    def __init__(self, lib):
+        self.lib = lib
+        lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pool = []
+
+    def block(self, n: int):
+        arr = (ctypes.c_void_p * n)()
+        for i in range(n):
+            e = ctypes.c_void_p()
+            rc = self.lib.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            arr[i] = e
+        self.pool.append(arr)
+        return arr
+
+    def elapsed_ms(self, a, b) -> float:
+        out = ctypes.c_float(0)
+        rc = self.lib.hipEventElapsedTime(ctypes.byref(out), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(out.value)
+
+    def destroy(self):
+        for arr in self.pool:
+            for e in arr:
+                self.lib.hipEventDestroy(e)
+        self.pool = []
+
+
+def cpu_baseline(cfg, W, seconds_hint: float = 20.0):
+    """The oracle, as it stands, on a bounded sample: every scale of layer 0 for
+    one (sequence, head) unit per host thread.  Extrapolated by unit count."""
+    import oracle
+    n_thr = oracle.num_threads()
+    units = list(range(min(2 * n_thr, cfg.n_seq * cfg.n_head)))
+    table = W.budget_table(cfg)
+    layer = 0
+    kp, vp = W.make_prefix(cfg, layer, "cpu", units)
+    src_k, src_v = kp.double().numpy(), vp.double().numpy()
+    # inputs are generated before the clock starts
+    steps = []
+    for k in range(1, cfg.n_scale + 1):
+        x = W.make_step_inputs(cfg, layer, k, "cpu", units)
+        steps.append((x.q.double().numpy(), x.k_cur.double().numpy(), x.v_cur.double().numpy(),
+                      W.window_indices(cfg, cfg.n_tokens(k)), table[layer][k - 1]))
+    t0 = time.perf_counter()
+    for (q, kc, vc, win, budget) in steps:
+        r = oracle.step(q, kc, vc, win, src_k, src_v, budget)
+        src_k, src_v = r["k_dst"], r["v_dst"]
+    dt = time.perf_counter() - t0
+    total_units = cfg.n_seq * cfg.n_head * cfg.n_layer
+    est_ms = dt * 1e3 * total_units / len(units)
+    return {
+        "value": est_ms, "unit": "ms per 13-scale image batch (extrapolated by unit count)",
+        "cores": n_thr, "kind": "oracle",
+        "sample": f"all {cfg.n_scale} scales of layer {layer} for {len(units)} of {cfg.n_seq * cfg.n_head} "
+                  f"(sequence, head) units, two per thread; {dt:.2f} s measured, "
+                  f"scaled by {total_units}/{len(units)} units x layers",
+        "sample_seconds": dt,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="2b_1024")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shared-inputs", action="store_true",
+                    help="reuse layer 0's Q/K/V in every layer (less memory, faster set-up)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2505_19602_amd as skv
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda"
+    cfg = W.get_config(args.config)
+    dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    S, H, d, Lyr, K = cfg.n_seq, cfg.n_head, cfg.head_dim, cfg.n_layer, cfg.n_scale
+    U = S * H
+    e = cfg.elem_bytes
+    shape = skv.Shape(S, H, d, dtype)
+    cap = W.dst_capacity(cfg)
+    table = W.budget_table(cfg)
+    log(f"{skv.version()}  workload {cfg.name}: S={S} H={H} d={d} layers={Lyr} scales={K} cap={cap}")
+
+    # ---- resident state: prefix caches, ping-pong caches, per-(layer, scale) inputs
+    t_setup = time.perf_counter()
+    prefix = [W.make_prefix(cfg, l, dev) for l in range(Lyr)]
+    bufs = [[(torch.empty(S, H, cap, d, dtype=dtype, device=dev), torch.empty(S, H, cap, d, dtype=dtype, device=dev))
+             for _ in range(2)] for _ in range(Lyr)]
+    inputs = {}
+    for k in range(1, K + 1):
+        for l in range(Lyr):
+            if args.shared_inputs and l > 0:
+                inputs[(l, k)] = inputs[(0, k)]
+            else:
+                inputs[(l, k)] = W.make_step_inputs(cfg, l, k, dev)
+        torch.cuda.synchronize()
+        log(f"inputs for scale {k}/{K} ready ({torch.cuda.memory_allocated() / 2**30:.1f} GiB resident)")
+    max_q = max(cfg.n_tokens(k) for k in range(1, K + 1))
+    ws = torch.empty(skv.workspace_bytes(shape, cap, max_q), dtype=torch.uint8, device=dev)
+    out = torch.empty(S, H, max_q, d, dtype=dtype, device=dev)
+    outs = {k: out.view(-1)[: U * cfg.n_tokens(k) * d].view(S, H, cfg.n_tokens(k), d) for k in range(1, K + 1)}
+    windows = {k: W.window_indices(cfg, cfg.n_tokens(k)) for k in range(1, K + 1)}
+    log(f"set-up {time.perf_counter() - t_setup:.1f} s")
+
+    events = HipEvents(skv.lib())
+
+    def run_sequence(ev_blocks=None):
+        """416 scalekv_step calls; returns per-call (layer, scale, cache_len, keep, n_cur)."""
+        meta = []
+        lens = [cfg.prefix] * Lyr
+        srcs = [prefix[l] for l in range(Lyr)]
+        i = 0
+        for k in range(1, K + 1):
+            n_cur = cfg.n_tokens(k)
+            for l in range(Lyr):
+                x = inputs[(l, k)]
+                dst = bufs[l][k % 2]
+                if ev_blocks is not None:
+                    skv.step_stage_events(ev_blocks[i])
+                new_len = skv.step(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
+                                   table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
+                meta.append((l, k, lens[l], new_len - n_cur, n_cur))
+                srcs[l], lens[l] = dst, new_len
+                i += 1
+        if ev_blocks is not None:
+            skv.step_stage_events(None)
+        return meta
+
+    n_calls = Lyr * K
+    for w in range(args.warmup):
+        run_sequence()
+        torch.cuda.synchronize()
+        log(f"warm-up {w + 1}/{args.warmup} done")
+
+    ev_steps = [[events.block(5) for _ in range(n_calls)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    meta = None
+    for s in range(args.steps):
+        meta = run_sequence(ev_steps[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    log(f"timed {args.steps} steps: {ms_per_step:.2f} ms per step")
+
+    # ---- per-stage totals from the events recorded inside the timed region
+    stage_names = ("score", "select", "compact", "attend")
+    stage_ms = {n: 0.0 for n in stage_names}
+    per_scale_ms = {k: 0.0 for k in range(1, K + 1)}
+    attend_big = dict(ms=0.0, flops=0.0, launches=0)      # the QB=2 MFMA kernel (n_cur > 128)
+    attend_all = dict(ms=0.0, flops=0.0)
+    compact_stat = dict(ms=0.0, bytes=0.0)
+    score_stat = dict(ms=0.0, bytes=0.0)
+    for s in range(args.steps):
+        for i, (l, k, cache_len, keep, n_cur) in enumerate(meta):
+            ev = ev_steps[s][i]
+            t = [events.elapsed_ms(ev[j], ev[j + 1]) for j in range(4)]
+            for n, x in zip(stage_names, t):
+                stage_ms[n] += x
+            per_scale_ms[k] += sum(t)
+            fl = 4.0 * n_cur * (keep + n_cur) * d * U
+            attend_all["ms"] += t[3]; attend_all["flops"] += fl
+            if n_cur > 128 and dtype == torch.bfloat16:
+                attend_big["ms"] += t[3]; attend_big["flops"] += fl; attend_big["launches"] += 1
+            compact_stat["ms"] += t[2]
+            compact_stat["bytes"] += 2.0 * 2.0 * (keep + n_cur) * d * e * U + (4.0 * keep * U if keep < cache_len else 0)
+            if 0 < keep < cache_len:
+                score_stat["ms"] += t[0]
+                score_stat["bytes"] += (cache_len * d * e + len(windows[k]) * d * e + 4.0 * cache_len) * U
+    events.destroy()
+    for n in stage_names:
+        stage_ms[n] /= args.steps
+    per_scale_ms = {str(k): v / args.steps for k, v in per_scale_ms.items()}
+
+    dom = attend_big if attend_big["launches"] else dict(ms=attend_all["ms"], flops=attend_all["flops"],
+                                                         launches=args.steps * n_calls)
+    achieved_tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+    roofline = {
+        "bound": "mfma", "kernel": "attend_mfma_kernel<128,2>" if attend_big["launches"] else "attend",
+        "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+        "launches": dom["launches"], "avg_launch_ms": dom["ms"] / max(1, dom["launches"]),
+        "flops_per_launch_avg": dom["flops"] / max(1, dom["launches"]),
+    }
+    compact_gbs = compact_stat["bytes"] / (compact_stat["ms"] * 1e-3) / 1e9 if compact_stat["ms"] > 0 else 0.0
+    score_gbs = score_stat["bytes"] / (score_stat["ms"] * 1e-3) / 1e9 if score_stat["ms"] > 0 else 0.0
+
+    result = {
+        "metric": "ScaleKV step ms per 1024^2 image batch (13 scales)" if cfg.name == "2b_1024"
+                  else f"ScaleKV step ms per image batch ({cfg.name})",
+        "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {S} sequences x {H} heads x d{d}, {Lyr} layers, {K} scales "
+                               f"({cfg.image_tokens} image tokens, {cfg.prefix}-token prefix), "
+                               f"{cfg.n_drafter} drafters at {cfg.drafter_frac:.0%} / {Lyr - cfg.n_drafter} refiners at "
+                               f"{cfg.refiner_frac:.0%} per scale, window {cfg.window}",
+                   "calls_per_step": n_calls, "shared_inputs": bool(args.shared_inputs)},
+        "roofline": roofline,
+        "stage_ms": stage_ms,
+        "per_scale_ms": per_scale_ms,
+        "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
+        "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS},
+        "score_hbm": {"achieved": score_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": score_gbs / PEAK_HBM_GBS},
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on its sample ...")
+        del inputs, bufs
+        torch.cuda.empty_cache()
+        result["cpu_baseline"] = cpu_baseline(cfg, W)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

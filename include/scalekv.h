@@ -104,8 +104,10 @@ scalekv_status scalekv_select(const scalekv_shape* shape, const float* scores, i
  * the same idx [S,H,keep]); then rows keep .. keep+n_cur-1 = the current map's
  * k_cur / v_cur [S,H,n_cur,d].  idx == NULL means the identity (keep all of
  * the first `keep` rows, keep <= cache_len).  k_cur/v_cur may be NULL iff
- * n_cur == 0.  Copies are bit-exact.  Source and destination caches must not
- * overlap.  Requires keep + n_cur <= dst capacity and idx entries in
+ * n_cur == 0.  Copies are bit-exact.  The byte spans of the two
+ * source caches and the two destination caches (first to last addressable
+ * element of each) must be pairwise disjoint, except that k_src may alias
+ * v_src.  Requires keep + n_cur <= dst capacity and idx entries in
  * [0, cache_len) (entries are not checked on the device). */
 scalekv_status scalekv_compact(const scalekv_shape* shape, const scalekv_kv* k_src,
                                const scalekv_kv* v_src, int32_t cache_len, const int32_t* idx,
@@ -135,6 +137,15 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                             int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
                             const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
                             int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Benchmark aid, not part of the method.  events: host array of 5 hipEvent_t
+ * (created by the caller with timing enabled), or NULL to switch off.  While
+ * set, every scalekv_step call of this thread records, on its stream, events[0]
+ * before the first kernel and events[1..4] after the score, select, compact and
+ * attend kernels respectively (stages that are skipped record their event
+ * anyway).  The array is read at each scalekv_step call and must stay valid until
+ * it is replaced or cleared. */
+scalekv_status scalekv_step_stage_events(void** events);
 
 /* Message for the calling thread's most recent non-OK status (static storage,
  * never NULL). */

@@ -19,7 +19,8 @@ MAX_WINDOW = 16
 
 EXPORTED_SYMBOLS = (
     "scalekv_workspace_bytes", "scalekv_score", "scalekv_select", "scalekv_compact",
-    "scalekv_attend", "scalekv_step", "scalekv_last_error", "scalekv_version",
+    "scalekv_attend", "scalekv_step", "scalekv_step_stage_events", "scalekv_last_error",
+    "scalekv_version",
 )
 
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE", 4: "HIP"}
@@ -76,7 +77,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(path)
         L.scalekv_last_error.restype = ctypes.c_char_p
         L.scalekv_version.restype = ctypes.c_char_p
-        for name in EXPORTED_SYMBOLS[:6]:
+        for name in EXPORTED_SYMBOLS[:7]:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -221,3 +222,9 @@ def step(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor
                               ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len), _ptr(out), _ptr(idx_out),
                               wp, wb, _stream()))
     return int(new_len.value)
+
+
+def step_stage_events(events) -> None:
+    """scalekv_step_stage_events: `events` is a ctypes array of 5 hipEvent_t
+    (c_void_p) or None."""
+    _check(lib().scalekv_step_stage_events(events))

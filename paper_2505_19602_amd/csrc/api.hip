@@ -13,6 +13,7 @@ using namespace scalekv;
 namespace {
 
 thread_local char g_err[256] = "no error";
+thread_local void** g_stage_events = nullptr;  // benchmark hook, see scalekv_step_stage_events
 
 scalekv_status fail(scalekv_status st, const char* fmt, ...) {
   va_list ap;
@@ -166,6 +167,11 @@ const char* scalekv_last_error(void) { return g_err; }
 
 const char* scalekv_version(void) { return "scalekv 0.1 gfx950"; }
 
+scalekv_status scalekv_step_stage_events(void** events) {
+  g_stage_events = events;
+  return SCALEKV_OK;
+}
+
 scalekv_status scalekv_workspace_bytes(const scalekv_shape* shape, int32_t max_cache_len,
                                        int32_t max_q, size_t* out) {
   SCALEKV_TRY(check_shape(shape));
@@ -306,8 +312,13 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
     return fail(SCALEKV_ERR_INVALID_ARG, "source and destination caches overlap");
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  void** ev = g_stage_events;
+  auto mark = [&](int i) -> hipError_t {
+    return ev ? hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) : hipSuccess;
+  };
   const int U = shape->n_seq * shape->n_head;
   const int32_t* idx = nullptr;  // identity unless a ranking is needed
+  SCALEKV_HIP(mark(0), "event record");
   if (ranks) {
     const WsLayout w = ws_layout(shape, cache_len);
     const ScoreWorkspace sw = score_ws(w, ws);
@@ -322,19 +333,24 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                 "score logits launch");
     SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
                 "score finalize launch");
+    SCALEKV_HIP(mark(1), "event record");
     SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, st), "select launch");
     idx = idx_ws;
-  } else if (idx_out && keep > 0) {
-    // keep == cache_len: the selection is the identity
-    SCALEKV_HIP(launch_select(U, nullptr, 0, cache_len, keep, idx_out, st), "select launch");
+  } else {
+    SCALEKV_HIP(mark(1), "event record");
+    if (idx_out && keep > 0)  // keep == cache_len: the selection is the identity
+      SCALEKV_HIP(launch_select(U, nullptr, 0, cache_len, keep, idx_out, st), "select launch");
   }
+  SCALEKV_HIP(mark(2), "event record");
   SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
                              view(k_src), view(v_src), idx, keep, k_cur, v_cur, n_cur, view(k_dst),
                              view(v_dst), st),
               "compact launch");
+  SCALEKV_HIP(mark(3), "event record");
   SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_cur,
                             view(k_dst), view(v_dst), keep + n_cur, resolve_scale(shape), out, st),
               "attend launch");
+  SCALEKV_HIP(mark(4), "event record");
   if (new_len_out) *new_len_out = keep + n_cur;
   return SCALEKV_OK;
 }
