@@ -16,6 +16,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 // =====================================================================
 // fp32 / generic kernel.  256 threads: 32 query rows x 8 lanes per row.
@@ -126,10 +127,20 @@ __global__ __launch_bounds__(256) void attend_simple_kernel(
 // matching V^T operand is one contiguous 16-byte LDS read.
 // =====================================================================
 constexpr int BN = 64;
+constexpr float kRescaleThreshold = 8.f;  // log2 units a row max may grow before O is rescaled
 
 __device__ __forceinline__ int pi32(int i) {  // swap bits 2 and 3
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
+
+template <int D>
+struct AttendLds {
+  static constexpr int KS = D + 8;    // LDS row stride of a K tile (elements)
+  static constexpr int VS = BN + 8;   // LDS row stride of a V^T tile
+  static constexpr int kTileK = BN * KS;
+  static constexpr int kTileV = D * VS;
+  static constexpr int kBytes = 2 * (kTileK + kTileV) * 2;  // two stages
+};
 
 template <int D, int QB>
 __global__ __launch_bounds__(256) void attend_mfma_kernel(
@@ -137,13 +148,14 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
     long long k_seq_stride, long long k_head_stride, const uint16_t* __restrict__ v,
     long long v_seq_stride, long long v_head_stride, int kv_len, int n_head, float scale_log2e,
     uint16_t* __restrict__ out) {
-  constexpr int KS = D + 8;    // LDS row stride of the K tile (elements)
-  constexpr int VS = BN + 8;   // LDS row stride of the V^T tile
+  using L = AttendLds<D>;
+  constexpr int KS = L::KS, VS = L::VS;
   constexpr int NSL = D / 16;  // k-slabs of the first product
   constexpr int NDB = D / 32;  // 32-channel blocks of the output
   constexpr int KV_LOADS = BN * D / 8 / 256;  // 16-byte vectors per thread per tile
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[BN * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t vt_lds[D * VS];
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  uint16_t* const k_lds0 = smem;
+  uint16_t* const vt_lds0 = smem + 2 * L::kTileK;
 
   const int unit = blockIdx.y;
   const int seq = unit / n_head, head = unit - seq * n_head;
@@ -174,17 +186,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[db][qb][r] = 0.f;
+  // m_run: the (possibly stale, see below) row max used as the exponent offset;
+  // l_run: this lane's share of the row sum (the two half-waves are added at the end).
   float m_run[QB], l_run[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
   // ---- staging maps
   // K tile: vector f = tid + 256*p covers row f/(D/8), 16-byte column f%(D/8).
-  // V tile: thread owns 4 consecutive keys x 8 consecutive channels.
+  // V tile: thread owns 4 consecutive keys x 8 consecutive channels and writes them transposed.
   constexpr int CPR = D / 8;           // 16-byte vectors per row
   const int v_cg = tid % CPR;          // channel group: channels 8*v_cg .. +7
   const int v_rg = tid / CPR;          // key group (4 keys each), 256/CPR groups per pass
-  constexpr int V_GROUPS = BN / 4;   // key groups per tile
+  constexpr int V_GROUPS = BN / 4;
   constexpr int V_PASSES = (V_GROUPS + 256 / CPR - 1) / (256 / CPR);
   uint4 k_stage[KV_LOADS];
   uint4 v_stage[V_PASSES][4];
@@ -209,7 +223,9 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
       }
     }
   };
-  auto store_lds = [&]() {
+  auto store_lds = [&](int stage) {
+    uint16_t* k_lds = k_lds0 + stage * L::kTileK;
+    uint16_t* vt_lds = vt_lds0 + stage * L::kTileV;
 #pragma unroll
     for (int p = 0; p < KV_LOADS; ++p) {
       const int f = tid + 256 * p;
@@ -240,11 +256,14 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
 
   const int n_tile = (kv_len + BN - 1) / BN;
   issue_loads(0);
+  store_lds(0);
+  __syncthreads();
   for (int t = 0; t < n_tile; ++t) {
-    __syncthreads();  // every wave is done reading the previous tile
-    store_lds();
-    __syncthreads();
-    if (t + 1 < n_tile) issue_loads((t + 1) * BN);
+    const int stage = t & 1;
+    const uint16_t* k_lds = k_lds0 + stage * L::kTileK;
+    const uint16_t* vt_lds = vt_lds0 + stage * L::kTileV;
+    const bool more = t + 1 < n_tile;
+    if (more) issue_loads((t + 1) * BN);  // lands in registers while this tile is computed
 
     // ---- S^T = K Q^T for two 32-key blocks
     f32x16 s[2][QB];
@@ -280,33 +299,55 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
           }
         }
     }
-    bf16x8 pf[QB][4];
+    // Row max of this tile.  The running offset m_run is only moved (and O, l
+    // rescaled) when some row's max grew by more than kRescaleThreshold in log2
+    // units; otherwise exp2 arguments stay <= the threshold, which fp32 and bf16
+    // hold without loss, and the accumulators are left alone.
+    float mx[QB];
+    bool grow = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float mx = m_run[qb];
+      float m = s[0][qb][0];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][qb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mxs = mx * scale_log2e;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qb] * scale_log2e - mxs);
-      m_run[qb] = mx;
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, s[kb][qb][r]);
+      m = fmaxf(m, __shfl_xor(m, 32));
+      mx[qb] = m;
+      grow |= (m - m_run[qb]) * scale_log2e > kRescaleThreshold;
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(m_run[qb], mx[qb]);
+        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * scale_log2e);
+        m_run[qb] = m_new;
+        l_run[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha;
+      }
+    }
+    bf16x8 pf[QB][4];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float off = m_run[qb] * scale_log2e;
       float rs = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][r], scale_log2e, -mxs));
-          rs += p;
-          pf[qb][2 * kb + r / 8][r % 8] = (__bf16)p;
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][r], scale_log2e, -off));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][r + 1], scale_log2e, -off));
+          const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+          pf[qb][2 * kb + r / 8][r % 8] = pr[0];
+          pf[qb][2 * kb + r / 8][r % 8 + 1] = pr[1];
+          // the row sum adds the rounded probabilities, the very numbers the MFMA multiplies by
+          rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);
         }
-      rs += __shfl_xor(rs, 32);
-      l_run[qb] = l_run[qb] * alpha + rs;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][qb][r] *= alpha;
+      l_run[qb] += rs;
     }
 
     // ---- O^T += V^T P^T
@@ -320,14 +361,19 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][sl], o[db][qb], 0, 0, 0);
       }
     }
+
+    // the other stage was last read one iteration ago, before the barrier below
+    if (more) store_lds(stage ^ 1);
+    __syncthreads();
   }
 
   // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int row = q_base + qb * 32 + j;
+    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
     if (row >= n_q) continue;
-    const float inv = 1.f / l_run[qb];
+    const float inv = 1.f / l_tot;
     uint16_t* orow = out + ((long long)unit * n_q + row) * D;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
@@ -341,6 +387,24 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
         *(uint2*)(orow + 32 * db + 8 * g + 4 * h) = pk;
       }
   }
+}
+
+template <int D, int QB>
+hipError_t launch_mfma(dim3 grid, hipStream_t stream, const uint16_t* q, int n_q, const uint16_t* k,
+                       KvView kv, const uint16_t* v, KvView vv, int kv_len, int n_head,
+                       float scale_log2e, uint16_t* out) {
+  static bool configured = false;  // LDS above 64 KB per workgroup has to be asked for once
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)attend_mfma_kernel<D, QB>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       AttendLds<D>::kBytes);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL((attend_mfma_kernel<D, QB>), grid, dim3(256), AttendLds<D>::kBytes, stream, q,
+                     n_q, k, kv.seq_stride, kv.head_stride, v, vv.seq_stride, vv.head_stride,
+                     kv_len, n_head, scale_log2e, out);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -369,24 +433,13 @@ hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q,
   const uint16_t* vp = (const uint16_t*)v.ptr;
   uint16_t* op = (uint16_t*)out;
   if (d == 128) {
-    if (n_q > 128) {
-      dim3 grid((n_q + 255) / 256, n_unit);
-      hipLaunchKernelGGL((attend_mfma_kernel<128, 2>), grid, dim3(256), 0, stream, qp, n_q, kp,
-                         k.seq_stride, k.head_stride, vp, v.seq_stride, v.head_stride, kv_len,
-                         n_head, scale_log2e, op);
-    } else {
-      dim3 grid((n_q + 127) / 128, n_unit);
-      hipLaunchKernelGGL((attend_mfma_kernel<128, 1>), grid, dim3(256), 0, stream, qp, n_q, kp,
-                         k.seq_stride, k.head_stride, vp, v.seq_stride, v.head_stride, kv_len,
-                         n_head, scale_log2e, op);
-    }
-  } else {
-    dim3 grid((n_q + 127) / 128, n_unit);
-    hipLaunchKernelGGL((attend_mfma_kernel<64, 1>), grid, dim3(256), 0, stream, qp, n_q, kp,
-                       k.seq_stride, k.head_stride, vp, v.seq_stride, v.head_stride, kv_len,
-                       n_head, scale_log2e, op);
+    if (n_q > 128)
+      return launch_attend_pipe(n_unit, n_head, q, n_q, k, v, kv_len, sm_scale, out, stream);
+    return launch_mfma<128, 1>(dim3((n_q + 127) / 128, n_unit), stream, qp, n_q, kp, k, vp, v,
+                               kv_len, n_head, scale_log2e, op);
   }
-  return hipGetLastError();
+  return launch_mfma<64, 1>(dim3((n_q + 127) / 128, n_unit), stream, qp, n_q, kp, k, vp, v, kv_len,
+                            n_head, scale_log2e, op);
 }
 
 }  // namespace scalekv

@@ -46,6 +46,10 @@ hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src,
 hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q, int n_q, KvView k,
                          KvView v, int kv_len, float sm_scale, void* out, hipStream_t stream);
 
+// bf16, head_dim 128 only: the pipelined kernel used when n_q is large
+hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
+                              int kv_len, float sm_scale, void* out, hipStream_t stream);
+
 // ---- device helpers ----
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
