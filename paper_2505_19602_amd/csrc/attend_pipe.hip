@@ -66,6 +66,14 @@ __device__ __forceinline__ int pi32(int i) {  // swap bits 2 and 3
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
 
+// Three-input max as one instruction and without the NaN-quieting pre-pass the compiler
+// puts in front of fmaxf on values it has not produced itself.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Lanes l and l^32 hold the two halves of one query row's statistics.  The swap
 // hands every lane {own value, partner's value} in some order; max and sum do not
 // care which is which.
@@ -101,25 +109,36 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
   // ---- tile loader: per thread 4 K vectors and 4 V vectors of 16 bytes.
   // Instruction p of wave w fills LDS rows 16w + 4p .. +3 (64 lanes x 16 B = 4 rows);
   // the lane that lands in chunk slot s of row r fetches global chunk s ^ f(r).
-  int ld_row[4], ld_kcol[4], ld_vcol[4];
+  int ld_row[4];
+  unsigned ld_kofs[4], ld_vofs[4];  // byte offset of this lane's vector inside a full tile
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int r = 16 * wave + 4 * p + (lane >> 4);
     ld_row[p] = r;
-    ld_kcol[p] = 16 * ((lane & 15) ^ (r & 15));
-    ld_vcol[p] = 16 * ((lane & 15) ^ ((r & 3) << 2));
+    ld_kofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ (r & 15));
+    ld_vofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ ((r & 3) << 2));
   }
   auto issue_tile = [&](int tile) {
     unsigned char* ks = k_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes;
     unsigned char* vs = v_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes;
+    const unsigned char* kt = ku + (long long)tile * kTileBytes;  // wave-uniform tile base
+    const unsigned char* vt = vu + (long long)tile * kTileBytes;
+    if ((tile + 1) * TN <= kv_len) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      // rows past the end re-read the last valid row: finite data that the mask zeroes out
-      const int g = min(tile * TN + ld_row[p], kv_len - 1);
-      __builtin_amdgcn_global_load_lds((glb_void*)(ku + (long long)g * kRowBytes + ld_kcol[p]),
-                                       (lds_void*)(ks + 4 * p * kRowBytes), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((glb_void*)(vu + (long long)g * kRowBytes + ld_vcol[p]),
-                                       (lds_void*)(vs + 4 * p * kRowBytes), 16, 0, 0);
+      for (int p = 0; p < 4; ++p) {
+        __builtin_amdgcn_global_load_lds((glb_void*)(kt + ld_kofs[p]), (lds_void*)(ks + 4 * p * kRowBytes), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(vt + ld_vofs[p]), (lds_void*)(vs + 4 * p * kRowBytes), 16, 0, 0);
+      }
+    } else {
+      // ragged last tile: rows past the end re-read the last valid row (finite data that
+      // the mask turns into zero weight)
+      const int last_row = kv_len - 1 - tile * TN;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int back = max(ld_row[p] - last_row, 0) * kRowBytes;
+        __builtin_amdgcn_global_load_lds((glb_void*)(kt + (ld_kofs[p] - back)), (lds_void*)(ks + 4 * p * kRowBytes), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void*)(vt + (ld_vofs[p] - back)), (lds_void*)(vs + 4 * p * kRowBytes), 16, 0, 0);
+      }
     }
   };
 
@@ -163,62 +182,76 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
   for (int qb = 0; qb < QB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
 
   // S(blk) = K Q^T for the 32 keys of block `blk`.
-  auto mfma_s = [&](int blk, f32x16 (&s_out)[QB]) {
-    const unsigned char* base = k_lds + ((blk >> 1) % kStages) * kTileBytes + (blk & 1) * 32 * kRowBytes;
+  // Operand fetches.  `ofs` = byte offset of the block inside the stage array (a constant
+  // in the main loop, where it folds into the instruction's offset field).
+  auto load_k = [&](int ofs, int sl) -> bf16x8 {  // K rows of the block, channels of slab sl
+    return *(const bf16x8*)(k_lds + ofs + k_ofs[sl]);
+  };
+  auto load_vt = [&](int ofs, int sl, int db) -> bf16x8 {  // V^T: channels of block db, keys of slab sl
+    const unsigned char* p = v_lds + ofs + sl * 16 * kRowBytes + v_ofs[db];
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(p + 4 * kRowBytes));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+  auto mfma_s_step = [&](const bf16x8& a, int sl, f32x16 (&s_out)[QB]) {
 #pragma unroll
-    for (int sl = 0; sl < 8; ++sl) {
-      const bf16x8 a = *(const bf16x8*)(base + k_ofs[sl]);
+    for (int qb = 0; qb < QB; ++qb) {
+      f32x16 c = s_out[qb];
+      if (sl == 0) {
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        f32x16 c = s_out[qb];
-        if (sl == 0) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) c[r] = 0.f;
-        }
-        s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][sl], c, 0, 0, 0);
+        for (int r = 0; r < 16; ++r) c[r] = 0.f;
       }
+      s_out[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][sl], c, 0, 0, 0);
     }
   };
-  // O^T += V^T(blk) P^T(blk)
-  auto mfma_pv = [&](int blk, const bf16x8 (&p_in)[QB][2]) {
-    const unsigned char* base = v_lds + ((blk >> 1) % kStages) * kTileBytes + (blk & 1) * 32 * kRowBytes;
+  auto mfma_pv_step = [&](const bf16x8& a, int sl, int db, const bf16x8 (&p_in)[QB][2]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+      o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_in[qb][sl], o[db][qb], 0, 0, 0);
+  };
+  // whole-block forms, used outside the pipelined regions
+  auto mfma_s = [&](int ofs, f32x16 (&s_out)[QB]) {
+#pragma unroll
+    for (int sl = 0; sl < 8; ++sl) mfma_s_step(load_k(ofs, sl), sl, s_out);
+  };
+  auto mfma_pv = [&](int ofs, const bf16x8 (&p_in)[QB][2]) {
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const unsigned char* p = base + sl * 16 * kRowBytes + v_ofs[db];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(p + 4 * kRowBytes));
-        const bf16x8 a = __builtin_bit_cast(
-            bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_in[qb][sl], o[db][qb], 0, 0, 0);
-      }
+      for (int db = 0; db < 4; ++db) mfma_pv_step(load_vt(ofs, sl, db), sl, db, p_in);
   };
-  // exponentials of block scores against offset `off`; returns the lane's row-sum share
-  auto exps = [&](const f32x16& s, float off, bf16x8 (&p)[2]) -> float {
+  // two scores -> two probabilities (bf16) against exponent offset `off`; the row-sum share
+  // adds the rounded values, the very numbers the MFMA multiplies by
+  auto exp_pair = [&](const f32x16& s, int r, float off, bf16x8 (&p)[2], float& rs) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -off));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[r + 1], scale_log2e, -off));
+    const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+    p[r / 8][r % 8] = pr[0];
+    p[r / 8][r % 8 + 1] = pr[1];
+    rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);
+  };
+  auto exps = [&](const f32x16& s, float off, bf16x8 (&p)[2]) -> float {
     float rs = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -off));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[r + 1], scale_log2e, -off));
-      const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
-      p[r / 8][r % 8] = pr[0];
-      p[r / 8][r % 8 + 1] = pr[1];
-      rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);  // sums what the MFMA will see
-    }
+    for (int r = 0; r < 16; r += 2) exp_pair(s, r, off, p, rs);
     return rs;
   };
 
   // One region: softmax of block `blk` (scores in s_in; register r = key 16(r/8) + 8h + r%8
-  // of the block) together with S(blk+1) -> s_out and P(blk-1) V(blk-1) from p_in.
-  // `mask` (only looked at when may_mask) hides keys at or beyond kv_len.
-  auto region = [&](auto has_prev, auto has_next, auto may_mask, bool mask, int blk,
-                    f32x16 (&s_in)[QB], f32x16 (&s_out)[QB], const bf16x8 (&p_in)[QB][2],
-                    bf16x8 (&p_out)[QB][2]) {
+  // of the block) together with S(blk+1) -> s_out (K block at k_next_ofs) and
+  // P(blk-1) V(blk-1) from p_in (V block at v_prev_ofs).  `mask` (only looked at when
+  // may_mask) hides keys at or beyond kv_len.
+  //
+  // The body is 16 steps.  Step i issues one MFMA pair (first the 8 slabs of S, then the 8
+  // (slab, channel block) pieces of PV), fetches the operand two steps ahead, and then does
+  // 1/16 of the softmax VALU work, which executes while the pair is in the matrix pipe.
+  // Scheduling fences keep the compiler from regrouping the steps.
+  auto region = [&](auto has_prev, auto has_next, auto may_mask, bool mask, int blk, int k_next_ofs,
+                    int v_prev_ofs, f32x16 (&s_in)[QB], f32x16 (&s_out)[QB],
+                    const bf16x8 (&p_in)[QB][2], bf16x8 (&p_out)[QB][2]) {
+    constexpr bool kPrev = decltype(has_prev)::value, kNext = decltype(has_next)::value;
     if constexpr (decltype(may_mask)::value) {
       if (mask) {
 #pragma unroll
@@ -231,38 +264,46 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
         }
       }
     }
-    __builtin_amdgcn_sched_barrier(0);  // nothing from before (tile requests, masking) mixes in
-    if constexpr (decltype(has_next)::value) mfma_s(blk + 1, s_out);
-    if constexpr (decltype(has_prev)::value) mfma_pv(blk - 1, p_in);
-
-    float mx[QB], rs[QB];
+    __builtin_amdgcn_sched_barrier(0);
+    auto fetch = [&](int i) -> bf16x8 {  // operand of step i
+      if (i < 8) return load_k(k_next_ofs, i);
+      return load_vt(v_prev_ofs, (i - 8) >> 2, (i - 8) & 3);
+    };
+    auto wanted = [&](int i) { return i < 8 ? kNext : (i < 16 ? kPrev : false); };
+    bf16x8 frag[3];
+    if (wanted(0)) frag[0] = fetch(0);
+    if (wanted(1)) frag[1] = fetch(1);
+    float mx[QB], rs[QB], off[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { rs[qb] = 0.f; off[qb] = m_run[qb] * scale_log2e; }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (wanted(i + 2)) frag[(i + 2) % 3] = fetch(i + 2);
+      if (wanted(i)) {
+        if (i < 8) mfma_s_step(frag[i % 3], i, s_out);
+        else mfma_pv_step(frag[i % 3], (i - 8) >> 2, (i - 8) & 3, p_in);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {  // VALU share of this step: one pair of exponentials and one piece of the row max
+        const int qb = i & 1, pair = i >> 1;
+        exp_pair(s_in[qb], 2 * pair, off[qb], p_out[qb], rs[qb]);
+        if (pair == 0) mx[qb] = max3(s_in[qb][0], s_in[qb][1], s_in[qb][2]);
+        else if (pair < 7) mx[qb] = max3(mx[qb], s_in[qb][2 * pair + 1], s_in[qb][2 * pair + 2]);
+        else mx[qb] = fmaxf(mx[qb], s_in[qb][15]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     bool grow = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float m = fmaxf(s_in[qb][0], s_in[qb][1]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) m = fmaxf(m, fmaxf(s_in[qb][r], s_in[qb][r + 1]));
-      m = both_halves_max(m);
-      mx[qb] = m;
-      grow |= (m - m_run[qb]) * scale_log2e > kRescaleThreshold;
-      rs[qb] = exps(s_in[qb], m_run[qb] * scale_log2e, p_out[qb]);
+      mx[qb] = both_halves_max(mx[qb]);
+      grow |= (mx[qb] - m_run[qb]) * scale_log2e > kRescaleThreshold;
     }
-    // Pin the speculative results before the branch: without this the compiler moves the
-    // exponentials onto the common path after it, away from the MFMAs they should hide under.
+    // Pin the speculative results before the branch: without this the compiler may move
+    // the exponentials onto the common path after it.
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       asm volatile("" : "+v"(rs[qb]), "+v"(p_out[qb][0]), "+v"(p_out[qb][1]));
-    }
-    // Issue order for the steady state: operand fetches run a few ahead, and every MFMA
-    // is followed by a share of the softmax VALU work that executes under it.
-    if constexpr (decltype(has_prev)::value && decltype(has_next)::value) {
-      __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 4, 0);
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kSchedValu, kValuPerMfma, 0);
-        if (i < 20) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
-      }
     }
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // cold: some row max moved a lot
       // O lives in accumulation registers, which only MFMA and the accvgpr moves can
@@ -308,12 +349,14 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
   f32x16 s_a[QB], s_b[QB];
   bf16x8 p_a[QB][2], p_b[QB][2];
 
+  auto blk_ofs = [](int blk) { return ((blk >> 1) % kStages) * kTileBytes + (blk & 1) * 32 * kRowBytes; };
+
   issue_tile(0);
   if (n_tile > 1) issue_tile(1);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   mfma_s(0, s_a);
-  region(no, yes, yes, ragged && n_tile == 1, 0, s_a, s_b, p_b, p_a);
+  region(no, yes, yes, ragged && n_tile == 1, 0, blk_ofs(1), 0, s_a, s_b, p_b, p_a);
 
   // Crossing from tile t to tile t+1: tile t+1 was requested a whole tile ago; once every
   // wave is past tile t-1 its stage is free for tile t+2.
@@ -324,17 +367,29 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
   };
   int t = 0;
   if (n_tile > 1) next_tile(0);
-  for (; t + 2 < n_tile; ++t) {  // both blocks touched here lie in full, interior tiles
-    region(yes, yes, no, false, 2 * t + 1, s_b, s_a, p_a, p_b);
-    region(yes, yes, no, false, 2 * t + 2, s_a, s_b, p_b, p_a);
+  // Main loop, three tiles per trip so that every LDS stage offset is a constant.  Tile
+  // t+u sits in stage u; all blocks touched lie in full, interior tiles.
+  for (; t + 4 < n_tile; t += 3) {
+#pragma unroll
+    for (int u = 0; u < 3; ++u) {
+      constexpr int kHalf = 32 * kRowBytes;
+      const int un = (u + 1) % 3;
+      region(yes, yes, no, false, 0, un * kTileBytes, u * kTileBytes, s_b, s_a, p_a, p_b);
+      region(yes, yes, no, false, 0, un * kTileBytes + kHalf, u * kTileBytes + kHalf, s_a, s_b, p_b, p_a);
+      next_tile(t + u + 1);
+    }
+  }
+  for (; t + 2 < n_tile; ++t) {  // left-over interior tiles, offsets computed at run time
+    region(yes, yes, no, false, 0, blk_ofs(2 * t + 2), blk_ofs(2 * t), s_b, s_a, p_a, p_b);
+    region(yes, yes, no, false, 0, blk_ofs(2 * t + 3), blk_ofs(2 * t + 1), s_a, s_b, p_b, p_a);
     next_tile(t + 1);
   }
   if (t + 1 < n_tile) {  // into the last tile, which may be ragged
-    region(yes, yes, no, false, 2 * t + 1, s_b, s_a, p_a, p_b);
-    region(yes, yes, yes, ragged, 2 * t + 2, s_a, s_b, p_b, p_a);
+    region(yes, yes, no, false, 0, blk_ofs(2 * t + 2), blk_ofs(2 * t), s_b, s_a, p_a, p_b);
+    region(yes, yes, yes, ragged, 2 * t + 2, blk_ofs(2 * t + 3), blk_ofs(2 * t + 1), s_a, s_b, p_b, p_a);
   }
-  region(yes, no, yes, ragged, 2 * n_tile - 1, s_b, s_a, p_a, p_b);
-  mfma_pv(2 * n_tile - 1, p_b);
+  region(yes, no, yes, ragged, 2 * n_tile - 1, 0, blk_ofs(2 * n_tile - 2), s_b, s_a, p_a, p_b);
+  mfma_pv(blk_ofs(2 * n_tile - 1), p_b);
 
   // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
 #pragma unroll
