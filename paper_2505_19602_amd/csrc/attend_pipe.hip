@@ -232,6 +232,15 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
     p[r / 8][r % 8 + 1] = pr[1];
     rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);
   };
+  auto exp_pair2 = [&](float x0, float x1, int r, float off, bf16x8 (&p)[2], float& rs) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(x0, scale_log2e, -off));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(x1, scale_log2e, -off));
+    const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+    p[r / 8][r % 8] = pr[0];
+    p[r / 8][r % 8 + 1] = pr[1];
+    rs = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rs, false);
+  };
   auto exps = [&](const f32x16& s, float off, bf16x8 (&p)[2]) -> float {
     float rs = 0.f;
 #pragma unroll
@@ -284,12 +293,17 @@ __global__ __launch_bounds__(256) void attend_pipe_kernel(
         else mfma_pv_step(frag[i % 3], (i - 8) >> 2, (i - 8) & 3, p_in);
       }
       __builtin_amdgcn_sched_barrier(0);
-      {  // VALU share of this step: one pair of exponentials and one piece of the row max
+      {  // VALU share of this step: one pair of exponentials and one piece of the row max.
+        // The scores sit in accumulation registers (where the MFMAs of the previous region
+        // left them, long enough ago for any wait state) and are fetched here, two at a
+        // time, rather than all at once behind the MFMA that produced them.
         const int qb = i & 1, pair = i >> 1;
-        exp_pair(s_in[qb], 2 * pair, off[qb], p_out[qb], rs[qb]);
-        if (pair == 0) mx[qb] = max3(s_in[qb][0], s_in[qb][1], s_in[qb][2]);
-        else if (pair < 7) mx[qb] = max3(mx[qb], s_in[qb][2 * pair + 1], s_in[qb][2 * pair + 2]);
-        else mx[qb] = fmaxf(mx[qb], s_in[qb][15]);
+        float x0, x1;
+        asm volatile("v_accvgpr_read_b32 %0, %2\n\tv_accvgpr_read_b32 %1, %3"
+                     : "=v"(x0), "=v"(x1)
+                     : "a"(s_in[qb][2 * pair]), "a"(s_in[qb][2 * pair + 1]));
+        exp_pair2(x0, x1, 2 * pair, off[qb], p_out[qb], rs[qb]);
+        mx[qb] = pair == 0 ? fmaxf(x0, x1) : max3(mx[qb], x0, x1);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
