@@ -127,16 +127,34 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
     ld_kofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ (r & 15));
     ld_vofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ ((r & 3) << 2));
   }
+  // The request itself is written in assembly on purpose: the compiler, when it knows
+  // about a global->LDS transfer, waits for it before the next LDS read of the same array,
+  // which would serialise the transfer of tile t+1 with the consumption of tile t.  Here
+  // the only wait is the explicit one in front of the barrier that publishes the tile.
+  auto dma16 = [&](const unsigned char* base_uniform, unsigned voff, unsigned lds_addr_uniform) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_addr_uniform), "v"(voff), "s"(base_uniform)
+        : "m0", "memory");
+  };
+  auto lds_addr = [](const unsigned char* p) -> unsigned {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
+  };
   auto issue_tile = [&](int tile) {
-    unsigned char* ks = k_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes;
-    unsigned char* vs = v_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes;
+    const unsigned ks = __builtin_amdgcn_readfirstlane(
+        lds_addr(k_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes));
+    const unsigned vs = __builtin_amdgcn_readfirstlane(
+        lds_addr(v_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes));
     const unsigned char* kt = ku + (long long)tile * kTileBytes;  // wave-uniform tile base
     const unsigned char* vt = vu + (long long)tile * kTileBytes;
     if ((tile + 1) * TN <= kv_len) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        __builtin_amdgcn_global_load_lds((glb_void*)(kt + ld_kofs[p]), (lds_void*)(ks + 4 * p * kRowBytes), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)(vt + ld_vofs[p]), (lds_void*)(vs + 4 * p * kRowBytes), 16, 0, 0);
+        dma16(kt, ld_kofs[p], ks + 4 * p * kRowBytes);
+        dma16(vt, ld_vofs[p], vs + 4 * p * kRowBytes);
       }
     } else {
       // ragged last tile: rows past the end re-read the last valid row (finite data that
@@ -145,8 +163,8 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int back = max(ld_row[p] - last_row, 0) * kRowBytes;
-        __builtin_amdgcn_global_load_lds((glb_void*)(kt + (ld_kofs[p] - back)), (lds_void*)(ks + 4 * p * kRowBytes), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void*)(vt + (ld_vofs[p] - back)), (lds_void*)(vs + 4 * p * kRowBytes), 16, 0, 0);
+        dma16(kt, ld_kofs[p] - back, ks + 4 * p * kRowBytes);
+        dma16(vt, ld_vofs[p] - back, vs + 4 * p * kRowBytes);
       }
     }
   };
