@@ -31,8 +31,9 @@
 // The V^T operand is read with the transposing LDS load (ds_read_b64_tr_b16):
 // inside a group of 16 lanes, lane i supplies the address of 4 elements and
 // receives element (i & 3) of the data addressed by lanes (i >> 2) + 4r, r = 0..3.
-// Two stages per workgroup; tile t+1 is requested right after the barrier that
-// retires tile t-1.
+// Two stages per workgroup; tile t+2 is requested right after the barrier in the
+// middle of tile t's second block, which is also the point from which tile t+1 may
+// be read.  LDS operands are requested one phase ahead of the MFMAs that use them.
 //
 // Softmax.  Exponent offsets m_run are only moved (and O, l rescaled) when some
 // row max grew by more than kRescaleThreshold in log2 units; until then exp2
@@ -227,25 +228,29 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
     return rs;
   };
 
-  // One block of 32 keys at byte offset `ofs` of the current stage; `first_key` is its key
-  // index, used only when `mask` asks for keys at or beyond kv_len to be hidden.
-  auto block = [&](int ofs, bool mask, int first_key) {
-    bf16x8 kf[8];
+  // ---- the phases of one block of 32 keys
+  auto fetch_k = [&](bf16x8 (&kf)[8], int ofs) {
 #pragma unroll
     for (int sl = 0; sl < 8; ++sl) kf[sl] = load_k(ofs, sl);
+  };
+  auto fetch_vt = [&](bf16x8 (&vf)[2][4], int ofs) {
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) vf[sl][db] = load_vt(ofs, sl, db);
+  };
+  auto scores = [&](const bf16x8 (&kf)[8]) -> f32x16 {
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int sl = 0; sl < 8; ++sl) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sl], qf[sl], s, 0, 0, 0);
-    // V^T operands are requested now so that they arrive while the softmax runs
-    bf16x8 vf[2][4];
-#pragma unroll
-    for (int sl = 0; sl < 2; ++sl)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) vf[sl][db] = load_vt(ofs, sl, db);
-
-    if (mask) {  // register r is key 16(r/8) + 8h + r%8 of the block
+    return s;
+  };
+  // softmax of the block's scores (register r = key 16(r/8) + 8h + r%8 of the block; `mask`
+  // hides keys at or beyond kv_len) followed by O^T += V^T P^T
+  auto softmax_pv = [&](f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key) {
+    if (mask) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (first_key + 16 * (r / 8) + 8 * h + (r % 8) >= kv_len) s[r] = -INFINITY;
@@ -273,19 +278,54 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[sl][db], pf[sl], o[db], 0, 0, 0);
   };
 
+  // Schedule.  LDS operands are always requested one phase before the MFMAs that use
+  // them: V^T of a block ahead of its S MFMAs, K of the next block ahead of the softmax.
+  // One barrier per tile, in the middle of the tile's second block: by then a wave has
+  // finished every LDS read of the tile (so its stage may be refilled) and has waited for
+  // its share of the next tile (so that tile may be read).  The fences stop the compiler
+  // from sinking the requests back next to their uses.
   const int n_tile = (kv_len + TN - 1) / TN;
+  constexpr int kHalf = 32 * kRowBytes;
+  bf16x8 kf[8], vf[2][4];
   issue_tile(0);
-  for (int t = 0; t < n_tile; ++t) {
-    // tile t has landed everywhere and nobody still reads tile t-1 ...
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    // ... so its stage can take tile t+1 while tile t is consumed
-    if (t + 1 < n_tile) issue_tile(t + 1);
-    const int ofs = (t % kStages) * kTileBytes;
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (n_tile > 1) issue_tile(1);
+  fetch_k(kf, 0);
+  // One tile (two blocks).  `ofs` / `next_ofs` are the byte offsets of this tile's and the
+  // next tile's stage; in the main loop they are constants and fold into the LDS
+  // instructions' offset fields.
+  auto tile = [&](int t, int ofs, int next_ofs) {
     const bool mask = (t + 1) * TN > kv_len;
-    block(ofs, mask, t * TN);
-    block(ofs + 32 * kRowBytes, mask, t * TN + 32);
+    // ---- first block of the tile
+    fetch_vt(vf, ofs);
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 s = scores(kf);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_k(kf, ofs + kHalf);
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_pv(s, vf, mask, t * TN);
+    // ---- second block
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_vt(vf, ofs + kHalf);
+    __builtin_amdgcn_sched_barrier(0);
+    s = scores(kf);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + 1 < n_tile) {
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (t + 2 < n_tile) issue_tile(t + 2);
+      fetch_k(kf, next_ofs);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    softmax_pv(s, vf, mask, t * TN + 32);
+  };
+  int t = 0;
+  for (; t + 1 < n_tile; t += 2) {  // t even: stage 0 then stage 1
+    tile(t, 0, kTileBytes);
+    tile(t + 1, kTileBytes, 0);
   }
+  if (t < n_tile) tile(t, 0, kTileBytes);
 
   // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
   {
