@@ -229,7 +229,7 @@ def main() -> int:
                                                          launches=args.steps * n_calls)
     achieved_tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
     roofline = {
-        "bound": "mfma", "kernel": "attend_mfma_kernel<128,2>" if attend_big["launches"] else "attend",
+        "bound": "mfma", "kernel": "attend_pipe_kernel" if attend_big["launches"] else "attend",
         "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": None,
         "launches": dom["launches"], "avg_launch_ms": dom["ms"] / max(1, dom["launches"]),
