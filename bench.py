@@ -109,6 +109,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="2b_1024")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--untimed-check", action="store_true",
+                    help="also time the same steps without the stage events, to show what the events cost")
     ap.add_argument("--shared-inputs", action="store_true",
                     help="reuse layer 0's Q/K/V in every layer (less memory, faster set-up)")
     args = ap.parse_args()
@@ -157,27 +159,33 @@ def main() -> int:
 
     events = HipEvents(skv.lib())
 
+    # Marshal the 416 calls once: the cache lengths follow from the budgets, so every
+    # argument of every call is known before anything runs.
+    calls, meta = [], []
+    lens = [cfg.prefix] * Lyr
+    srcs = [prefix[l] for l in range(Lyr)]
+    for k in range(1, K + 1):
+        n_cur = cfg.n_tokens(k)
+        for l in range(Lyr):
+            x = inputs[(l, k)]
+            dst = bufs[l][k % 2]
+            call = skv.PreparedStep(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
+                                    table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
+            calls.append(call)
+            meta.append((l, k, lens[l], call.new_len - n_cur, n_cur))
+            srcs[l], lens[l] = dst, call.new_len
+    stream_ptr = torch.cuda.current_stream().cuda_stream
+
     def run_sequence(ev_blocks=None):
-        """416 scalekv_step calls; returns per-call (layer, scale, cache_len, keep, n_cur)."""
-        meta = []
-        lens = [cfg.prefix] * Lyr
-        srcs = [prefix[l] for l in range(Lyr)]
-        i = 0
-        for k in range(1, K + 1):
-            n_cur = cfg.n_tokens(k)
-            for l in range(Lyr):
-                x = inputs[(l, k)]
-                dst = bufs[l][k % 2]
-                if ev_blocks is not None:
-                    skv.step_stage_events(ev_blocks[i])
-                new_len = skv.step(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
-                                   table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
-                meta.append((l, k, lens[l], new_len - n_cur, n_cur))
-                srcs[l], lens[l] = dst, new_len
-                i += 1
-        if ev_blocks is not None:
+        """the whole multi-scale sequence: one scalekv_step per (scale, layer)"""
+        if ev_blocks is None:
+            for call in calls:
+                call(stream_ptr)
+        else:
+            for call, ev in zip(calls, ev_blocks):
+                skv.step_stage_events(ev)
+                call(stream_ptr)
             skv.step_stage_events(None)
-        return meta
 
     n_calls = Lyr * K
     for w in range(args.warmup):
@@ -188,13 +196,22 @@ def main() -> int:
     ev_steps = [[events.block(5) for _ in range(n_calls)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    meta = None
     for s in range(args.steps):
-        meta = run_sequence(ev_steps[s])
+        run_sequence(ev_steps[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     log(f"timed {args.steps} steps: {ms_per_step:.2f} ms per step")
+
+    ms_no_events = None
+    if args.untimed_check:
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for s in range(args.steps):
+            run_sequence()
+        torch.cuda.synchronize()
+        ms_no_events = (time.perf_counter() - t1) * 1e3 / args.steps
+        log(f"same steps without stage events: {ms_no_events:.2f} ms per step")
 
     # ---- per-stage totals from the events recorded inside the timed region
     stage_names = ("score", "select", "compact", "attend")
@@ -251,6 +268,7 @@ def main() -> int:
                    "calls_per_step": n_calls, "shared_inputs": bool(args.shared_inputs)},
         "roofline": roofline,
         "stage_ms": stage_ms,
+        "ms_per_step_without_stage_events": ms_no_events,
         "per_scale_ms": per_scale_ms,
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS},

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     compact,
     attend,
     step,
+    PreparedStep,
     step_stage_events,
     MAX_WINDOW,
     EXPORTED_SYMBOLS,

@@ -224,6 +224,50 @@ def step(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor
     return int(new_len.value)
 
 
+class PreparedStep:
+    """One scalekv_step call with every argument already marshalled.  Building it does
+    all the checks that `step` does; calling it only crosses into C, which matters for
+    the small scales where a call's own work is a few microseconds.  Holds references to
+    its tensors so the pointers stay valid."""
+
+    __slots__ = ("_args", "_keep", "new_len", "_refs", "_fn")
+
+    def __init__(self, shape: Shape, q, k_cur, v_cur, win_idx, k_src, v_src, cache_len, budget,
+                 k_dst, v_dst, out, idx_out, ws):
+        n_cur = q.shape[2]
+        _dense(q, shape, n_cur, "q"); _dense(k_cur, shape, n_cur, "k_cur"); _dense(v_cur, shape, n_cur, "v_cur")
+        _dense(out, shape, n_cur, "out")
+        keep = max(0, min(int(budget), int(cache_len)))
+        if idx_out is not None:
+            if idx_out.dtype != torch.int32 or not idx_out.is_cuda or not idx_out.is_contiguous() \
+                    or tuple(idx_out.shape) != (shape.n_seq, shape.n_head, keep):
+                raise ScaleKVError(1, f"idx_out must be a contiguous int32 device tensor [S,H,{keep}]")
+        win = (ctypes.c_int32 * max(1, len(win_idx)))(*[int(w) for w in win_idx])
+        cs = shape.c()
+        a, b = _kv(k_src, shape, "k_src"), _kv(v_src, shape, "v_src")
+        c, d = _kv(k_dst, shape, "k_dst"), _kv(v_dst, shape, "v_dst")
+        wp, wb = _ws(ws)
+        new_len = ctypes.c_int32(-1)
+        self._refs = (cs, win, a, b, c, d, new_len, q, k_cur, v_cur, k_src, v_src, k_dst, v_dst, out, idx_out, ws)
+        self._args = [ctypes.byref(cs), _ptr(q), _ptr(k_cur), _ptr(v_cur), ctypes.c_int32(n_cur), win,
+                      ctypes.c_int32(len(win_idx)), ctypes.byref(a), ctypes.byref(b), ctypes.c_int32(cache_len),
+                      ctypes.c_int32(budget), ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len), _ptr(out),
+                      _ptr(idx_out), wp, wb, None]
+        self._keep = keep
+        self.new_len = keep + n_cur
+        self._fn = lib().scalekv_step
+
+    def __call__(self, stream_ptr: Optional[int] = None) -> int:
+        """Enqueue on `stream_ptr` (a hipStream_t as int) or on torch's current stream."""
+        args = self._args
+        args[-1] = ctypes.c_void_p(stream_ptr if stream_ptr is not None
+                                   else torch.cuda.current_stream().cuda_stream)
+        status = self._fn(*args)
+        if status != 0:
+            _check(status)
+        return self.new_len
+
+
 def step_stage_events(events) -> None:
     """scalekv_step_stage_events: `events` is a ctypes array of 5 hipEvent_t
     (c_void_p) or None."""

@@ -21,7 +21,7 @@ struct WindowRows {
 };
 
 struct ScoreWorkspace {
-  float* logits;    // [U][kMaxWindow][len_pad]
+  float* logits;    // [U][len_pad][kMaxWindow]  (key-major: the 16 window logits of a key are 64 B)
   float* partial;   // [U][n_chunk][2][kMaxWindow]  (row max, row sum of exp(logit - max))
   int len_pad;
   int n_chunk;

@@ -3,7 +3,8 @@
 // reported as log s_i.
 //
 // Two kernels.  `logits` streams the cached keys once (the HBM-bound part),
-// writes the fp32 logits of the <=16 window rows and, per 256-key chunk, each
+// writes the fp32 logits of the <=16 window rows (key-major, 64 B per key) and, per
+// 256-key chunk, each
 // row's running max and sum of exp.  `finalize` merges the chunk statistics
 // into the row normalisers and folds the rows with a log-sum-exp, so no
 // probability is ever rounded below fp32 and nothing underflows.
@@ -61,12 +62,17 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
     }
   }
 
-  float* lg = ws.logits + (long long)unit * kMaxWindow * ws.len_pad;
+  float* lg = ws.logits + ((long long)unit * ws.len_pad + key) * kMaxWindow;
   const int lane = tid & 63, wave = tid >> 6;
+  if (valid) {
+#pragma unroll
+    for (int j4 = 0; j4 < kMaxWindow; j4 += 4)
+      *(float4*)(lg + j4) = make_float4(acc[j4] * sm_scale, acc[j4 + 1] * sm_scale,
+                                        acc[j4 + 2] * sm_scale, acc[j4 + 3] * sm_scale);
+  }
 #pragma unroll
   for (int j = 0; j < kMaxWindow; ++j) {
     const float x = valid ? acc[j] * sm_scale : -INFINITY;
-    if (valid && j < n_win) lg[(long long)j * ws.len_pad + key] = x;
     float m = x;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
@@ -84,6 +90,91 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
       if (red_max[w][tid] > -INFINITY) ssum += red_sum[w][tid] * expf(red_max[w][tid] - m);
     float* part = ws.partial + ((long long)unit * ws.n_chunk + blockIdx.x) * 2 * kMaxWindow;
     part[tid] = m;
+    part[kMaxWindow + tid] = ssum;
+  }
+}
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// bf16 logits kernel: the HBM-bound part of the score.  Each wave multiplies 64 keys
+// by the 16 window queries with MFMA 16x16x32 (A = key rows read straight from global
+// memory, 16 bytes per lane, every byte of every key row exactly once; B = window
+// queries in registers).  All of a wave's key vectors are requested before the first
+// MFMA so that 16 KB per wave are in flight.
+//   A (16 x 32): lane holds row l%16, k-indices 8(l/16)..+7
+//   B (32 x 16): lane holds column l%16, k-indices 8(l/16)..+7
+//   C (16 x 16): lane holds column l%16, rows 4(l/16) + v, v = 0..3
+template <int D>
+__global__ __launch_bounds__(kThreads) void score_logits_mfma_kernel(
+    const uint16_t* __restrict__ q, long long q_unit_stride, WindowRows rows, int n_win,
+    const uint16_t* __restrict__ k, long long k_seq_stride, long long k_head_stride, int n_head,
+    int cache_len, float sm_scale, ScoreWorkspace ws) {
+  constexpr int NSL = D / 32;  // k-slabs
+  constexpr int NT = 4;        // 16-key tiles per wave
+  __shared__ float red_max[kThreads / 64][kMaxWindow];
+  __shared__ float red_sum[kThreads / 64][kMaxWindow];
+  const int unit = blockIdx.y;
+  const int seq = unit / n_head, head = unit - seq * n_head;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i = lane & 15, g = lane >> 4;
+  const uint16_t* qu = q + unit * q_unit_stride;
+  const uint16_t* ku = k + seq * k_seq_stride + head * k_head_stride;
+
+  bf16x8 qf[NSL];
+#pragma unroll
+  for (int sl = 0; sl < NSL; ++sl) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (i < n_win) raw = *(const uint4*)(qu + (long long)rows.row[i] * D + 32 * sl + 8 * g);
+    qf[sl] = __builtin_bit_cast(bf16x8, raw);
+  }
+  const int key0 = blockIdx.x * kScoreChunk + wave * (16 * NT);
+  bf16x8 kf[NT][NSL];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int key = min(key0 + 16 * t + i, cache_len - 1);  // clamp: legal address, value unused
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl)
+      kf[t][sl] = __builtin_bit_cast(bf16x8, *(const uint4*)(ku + (long long)key * D + 32 * sl + 8 * g));
+  }
+  float m = -INFINITY;
+  f32x4 c[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sl = 0; sl < NSL; ++sl)
+      c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][sl], qf[sl], c[t], 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int key = key0 + 16 * t + 4 * g + v;
+      c[t][v] = key < cache_len ? c[t][v] * sm_scale : -INFINITY;
+      m = fmaxf(m, c[t][v]);
+      if (key < cache_len) ws.logits[((long long)unit * ws.len_pad + key) * kMaxWindow + i] = c[t][v];
+    }
+  }
+  // row statistics of window row i over this wave's 64 keys, then over the workgroup
+  m = fmaxf(m, __shfl_xor(m, 16));
+  m = fmaxf(m, __shfl_xor(m, 32));
+  float e = 0.f;
+  if (m > -INFINITY) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) e += expf(c[t][v] - m);
+  }
+  e += __shfl_xor(e, 16);
+  e += __shfl_xor(e, 32);
+  if (lane < kMaxWindow) { red_max[wave][lane] = m; red_sum[wave][lane] = e; }
+  __syncthreads();
+  if (tid < kMaxWindow) {
+    float mm = -INFINITY;
+    for (int w = 0; w < kThreads / 64; ++w) mm = fmaxf(mm, red_max[w][tid]);
+    float ssum = 0.f;
+    for (int w = 0; w < kThreads / 64; ++w)
+      if (red_max[w][tid] > -INFINITY) ssum += red_sum[w][tid] * expf(red_max[w][tid] - mm);
+    float* part = ws.partial + ((long long)unit * ws.n_chunk + blockIdx.x) * 2 * kMaxWindow;
+    part[tid] = mm;
     part[kMaxWindow + tid] = ssum;
   }
 }
@@ -112,12 +203,17 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(int n_win, int cach
   __syncthreads();
   const int key = blockIdx.x * 256 + tid;
   if (key >= cache_len) return;
-  const float* lg = ws.logits + (long long)unit * kMaxWindow * ws.len_pad + key;
+  const float* lg = ws.logits + ((long long)unit * ws.len_pad + key) * kMaxWindow;
   float la[kMaxWindow];
+#pragma unroll
+  for (int j4 = 0; j4 < kMaxWindow; j4 += 4) {
+    const float4 x = *(const float4*)(lg + j4);
+    la[j4] = x.x; la[j4 + 1] = x.y; la[j4 + 2] = x.z; la[j4 + 3] = x.w;
+  }
   float top = -INFINITY;
 #pragma unroll
   for (int j = 0; j < kMaxWindow; ++j) {
-    la[j] = j < n_win ? lg[(long long)j * ws.len_pad] - row_shift[j] : -INFINITY;
+    la[j] = j < n_win ? la[j] - row_shift[j] : -INFINITY;
     top = fmaxf(top, la[j]);
   }
   float acc = 0.f;
@@ -152,8 +248,16 @@ hipError_t launch_score_logits(int dtype, int n_seq, int n_head, int d, const vo
   if (dtype == 0)
     return launch_logits_t<float>(n_seq, n_head, d, q, q_unit_stride, rows, n_win, k, cache_len,
                                   sm_scale, ws, stream);
-  return launch_logits_t<bf16_t>(n_seq, n_head, d, q, q_unit_stride, rows, n_win, k, cache_len,
-                                 sm_scale, ws, stream);
+  dim3 grid(ws.n_chunk, n_seq * n_head);
+  if (d == 128)
+    hipLaunchKernelGGL((score_logits_mfma_kernel<128>), grid, dim3(kThreads), 0, stream,
+                       (const uint16_t*)q, q_unit_stride, rows, n_win, (const uint16_t*)k.ptr,
+                       k.seq_stride, k.head_stride, n_head, cache_len, sm_scale, ws);
+  else
+    hipLaunchKernelGGL((score_logits_mfma_kernel<64>), grid, dim3(kThreads), 0, stream,
+                       (const uint16_t*)q, q_unit_stride, rows, n_win, (const uint16_t*)k.ptr,
+                       k.seq_stride, k.head_stride, n_head, cache_len, sm_scale, ws);
+  return hipGetLastError();
 }
 
 hipError_t launch_score_finalize(int n_unit, int n_win, int cache_len, ScoreWorkspace ws,
