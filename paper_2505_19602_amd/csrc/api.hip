@@ -331,10 +331,17 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                                     (long long)n_cur * shape->head_dim, rows, n_win, view(k_src),
                                     cache_len, resolve_scale(shape), sw, st),
                 "score logits launch");
-    SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
-                "score finalize launch");
     SCALEKV_HIP(mark(1), "event record");
-    SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, st), "select launch");
+    // the finalisation of the score is fused into the select; very long caches take the
+    // two-kernel route through the scores buffer
+    hipError_t fused = launch_select_from_logits(U, n_win, sw, cache_len, keep, idx_ws, st);
+    if (fused == hipErrorNotSupported) {
+      SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
+                  "score finalize launch");
+      SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, st), "select launch");
+    } else {
+      SCALEKV_HIP(fused, "fused select launch");
+    }
     idx = idx_ws;
   } else {
     SCALEKV_HIP(mark(1), "event record");

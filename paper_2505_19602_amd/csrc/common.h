@@ -40,6 +40,10 @@ hipError_t launch_score_finalize(int n_unit, int n_win, int cache_len, ScoreWork
                                  hipStream_t stream);
 hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
                          int cache_len, int keep, int32_t* idx, hipStream_t stream);
+// select straight from the logits workspace (score finalisation fused in); returns
+// hipErrorNotSupported when the unit is too long for the fused kernel
+hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
+                                     int keep, int32_t* idx, hipStream_t stream);
 hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src, KvView v_src,
                           const int32_t* idx, int keep, const void* k_cur, const void* v_cur,
                           int n_cur, KvView k_dst, KvView v_dst, hipStream_t stream);
@@ -76,6 +80,39 @@ struct Elem<bf16_t> {
     f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
   }
 };
+
+// ---- shared between the score finalisation and the fused select ----
+// Row normaliser of window row j: max_j + log Z_j from the per-chunk (max, sum exp) pairs.
+__device__ __forceinline__ float score_row_shift(const ScoreWorkspace& ws, int unit, int j) {
+  const float* part = ws.partial + (long long)unit * ws.n_chunk * 2 * kMaxWindow;
+  float m = -INFINITY;
+  for (int c = 0; c < ws.n_chunk; ++c) m = fmaxf(m, part[c * 2 * kMaxWindow + j]);
+  float z = 0.f;
+  for (int c = 0; c < ws.n_chunk; ++c)
+    z += part[c * 2 * kMaxWindow + kMaxWindow + j] * expf(part[c * 2 * kMaxWindow + j] - m);
+  return m + logf(z);
+}
+// log s_i = logsumexp_j(logit[i][j] - shift_j) for one key; row_shift lives in LDS.
+__device__ __forceinline__ float score_log_sum(const ScoreWorkspace& ws, int unit, int key, int n_win,
+                                               const float* row_shift) {
+  const float* lg = ws.logits + ((long long)unit * ws.len_pad + key) * kMaxWindow;
+  float la[kMaxWindow];
+#pragma unroll
+  for (int j4 = 0; j4 < kMaxWindow; j4 += 4) {
+    const float4 x = *(const float4*)(lg + j4);
+    la[j4] = x.x; la[j4 + 1] = x.y; la[j4 + 2] = x.z; la[j4 + 3] = x.w;
+  }
+  float top = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < kMaxWindow; ++j) {
+    la[j] = j < n_win ? la[j] - row_shift[j] : -INFINITY;
+    top = fmaxf(top, la[j]);
+  }
+  float acc = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMaxWindow; ++j) acc += j < n_win ? expf(la[j] - top) : 0.f;
+  return top + logf(acc);
+}
 
 // round-to-nearest-even float -> bf16 bits (NaN kept quiet)
 __device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {

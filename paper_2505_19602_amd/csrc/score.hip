@@ -187,39 +187,11 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(int n_win, int cach
   __shared__ float row_shift[kMaxWindow];  // max_j + log Z_j
   const int unit = blockIdx.y;
   const int tid = threadIdx.x;
-  if (tid < kMaxWindow) {
-    float shift = 0.f;
-    if (tid < n_win) {
-      const float* part = ws.partial + (long long)unit * ws.n_chunk * 2 * kMaxWindow;
-      float m = -INFINITY;
-      for (int c = 0; c < ws.n_chunk; ++c) m = fmaxf(m, part[c * 2 * kMaxWindow + tid]);
-      float z = 0.f;
-      for (int c = 0; c < ws.n_chunk; ++c)
-        z += part[c * 2 * kMaxWindow + kMaxWindow + tid] * expf(part[c * 2 * kMaxWindow + tid] - m);
-      shift = m + logf(z);
-    }
-    row_shift[tid] = shift;
-  }
+  if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
   __syncthreads();
   const int key = blockIdx.x * 256 + tid;
   if (key >= cache_len) return;
-  const float* lg = ws.logits + ((long long)unit * ws.len_pad + key) * kMaxWindow;
-  float la[kMaxWindow];
-#pragma unroll
-  for (int j4 = 0; j4 < kMaxWindow; j4 += 4) {
-    const float4 x = *(const float4*)(lg + j4);
-    la[j4] = x.x; la[j4 + 1] = x.y; la[j4 + 2] = x.z; la[j4 + 3] = x.w;
-  }
-  float top = -INFINITY;
-#pragma unroll
-  for (int j = 0; j < kMaxWindow; ++j) {
-    la[j] = j < n_win ? la[j] - row_shift[j] : -INFINITY;
-    top = fmaxf(top, la[j]);
-  }
-  float acc = 0.f;
-#pragma unroll
-  for (int j = 0; j < kMaxWindow; ++j) acc += j < n_win ? expf(la[j] - top) : 0.f;
-  log_scores[unit * score_unit_stride + key] = top + logf(acc);
+  log_scores[unit * score_unit_stride + key] = score_log_sum(ws, unit, key, n_win, row_shift);
 }
 
 template <typename T>

@@ -19,12 +19,17 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-template <bool IN_LDS>
+// FUSED: the scores are not read but formed here from the logits workspace (the score
+// finalisation), so the fused step neither writes nor re-reads them.
+template <bool IN_LDS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
                                                           long long score_unit_stride,
                                                           int cache_len, int keep,
-                                                          int32_t* __restrict__ idx) {
+                                                          int32_t* __restrict__ idx,
+                                                          ScoreWorkspace ws, int n_win) {
+  static_assert(IN_LDS || !FUSED, "the fused form keeps its keys in LDS");
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
+  __shared__ float row_shift[kMaxWindow];
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sel_bin, sel_remaining;
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
@@ -36,7 +41,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
     if constexpr (IN_LDS) return keys[i];
     else return order_key(s[i]);
   };
-  if constexpr (IN_LDS) {
+  if constexpr (FUSED) {
+    if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
+    __syncthreads();
+    for (int i = tid; i < cache_len; i += kThreads)
+      keys[i] = order_key(score_log_sum(ws, unit, i, n_win, row_shift));
+  } else if constexpr (IN_LDS) {
     for (int i = tid; i < cache_len; i += kThreads) keys[i] = order_key(s[i]);
   }
 
@@ -134,12 +144,22 @@ hipError_t launch_select(int n_unit, const float* scores, long long score_unit_s
                        idx, keep, total);
     return hipGetLastError();
   }
+  const ScoreWorkspace none{nullptr, nullptr, 0, 0};
   if (cache_len <= kLdsKeys)
-    hipLaunchKernelGGL(select_kernel<true>, dim3(n_unit), dim3(kThreads), 0, stream, scores,
-                       score_unit_stride, cache_len, keep, idx);
+    hipLaunchKernelGGL((select_kernel<true, false>), dim3(n_unit), dim3(kThreads), 0, stream,
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0);
   else
-    hipLaunchKernelGGL(select_kernel<false>, dim3(n_unit), dim3(kThreads), 0, stream, scores,
-                       score_unit_stride, cache_len, keep, idx);
+    hipLaunchKernelGGL((select_kernel<false, false>), dim3(n_unit), dim3(kThreads), 0, stream,
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
+                                     int keep, int32_t* idx, hipStream_t stream) {
+  if (cache_len > kLdsKeys) return hipErrorNotSupported;
+  if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
+  hipLaunchKernelGGL((select_kernel<true, true>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
+                     0, cache_len, keep, idx, ws, n_win);
   return hipGetLastError();
 }
 

@@ -176,7 +176,7 @@ def test_attend_closed_forms_on_gpu():
 
 # ------------------------------------------------------------------- step --
 
-def _run_chain(cfg, layers, unit_ids, check_all_units):
+def _run_chain(cfg, layers, unit_ids, check_all_units, last_scale=None):
     """Run all scales of `cfg` for the given layers on the GPU through
     scalekv_step and follow each (layer, unit) with the oracle."""
     dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
@@ -194,7 +194,7 @@ def _run_chain(cfg, layers, unit_ids, check_all_units):
         src_k, src_v, cache_len = kp, vp, cfg.prefix
         u_sel = list(range(S * H)) if check_all_units else unit_ids
         ref_k = units(kp)[u_sel].double().numpy(); ref_v = units(vp)[u_sel].double().numpy()
-        for k in range(1, cfg.n_scale + 1):
+        for k in range(1, (last_scale or cfg.n_scale) + 1):
             _note(f"step cfg={cfg.name} layer={layer} scale={k} cache_len={cache_len}")
             x = W.make_step_inputs(cfg, layer, k, DEV)
             n_cur, budget = cfg.n_tokens(k), table[layer][k - 1]
@@ -235,6 +235,42 @@ def test_step_chain_2b_512_sampled_units():
     stats = _run_chain(cfg, [0, 17], [0, 5, 15], False)
     _note(f"2b_512: {stats}")
     assert stats["exact"] > 0
+
+
+def test_step_chain_8b_shape_heavy_tailed_keys():
+    """40-layer / 32-head shape with Student-t keys (near-ties, underflow): the first nine
+    scales of two layers on all 512 units, three of them followed by the oracle."""
+    cfg = W.get_config("8b_1024")
+    stats = _run_chain(cfg, [0, 33], [0, 77, 511], False, last_scale=9)
+    _note(f"8b_1024: {stats}")
+    assert stats["exact"] + stats["band"] == 2 * 9 * 3
+
+
+def test_step_long_cache_and_other_shapes():
+    """cache longer than the fused select holds in LDS; head_dim 64 in bf16; fp32 with head_dim 128"""
+    for dtype, d, L, n_cur, budget in ((torch.bfloat16, 128, 13000, 40, 700), (torch.bfloat16, 64, 900, 150, 333),
+                                       (torch.float32, 128, 300, 50, 64)):
+        _note(f"step dtype={dtype} d={d} L={L} n_cur={n_cur} budget={budget}")
+        S, H = 1, 2
+        shape = skv.Shape(S, H, d, dtype)
+        q, kc, vc = (_rand(60 + i, (S, H, n_cur, d), dtype) for i in range(3))
+        ks, vs = _rand(63, (S, H, L, d), dtype), _rand(64, (S, H, L, d), dtype)
+        ws = torch.empty(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+        win = list(range(n_cur - 16, n_cur))
+        kd = torch.zeros(S, H, budget + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+        out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+        idx = torch.full((S, H, budget), -1, dtype=torch.int32, device=DEV)
+        new_len = skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), win, ks.to(DEV), vs.to(DEV), L, budget,
+                           kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        assert new_len == budget + n_cur
+        g_idx = idx.cpu().numpy().reshape(S * H, budget)
+        own = oracle.step(units(q), units(kc), units(vc), win, units(ks), units(vs), budget)
+        for u in range(S * H):
+            check_indices(g_idx[u], own["scores"][u], budget, own["idx"][u])
+        ref = oracle.step(units(q), units(kc), units(vc), win, units(ks), units(vs), budget, force_idx=g_idx)
+        assert np.array_equal(units(kd)[:, :new_len].double().numpy(), ref["k_dst"])
+        check_output(out, ref["out"], dtype, f"step d={d} L={L}")
 
 
 def test_step_edge_budgets():
