@@ -143,7 +143,8 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
  * set, every scalekv_step call of this thread records, on its stream, events[0]
  * before the first kernel and events[1..4] after the score, select, compact and
  * attend kernels respectively (stages that are skipped record their event
- * anyway).  The array is read at each scalekv_step call and must stay valid until
+ * anyway).  A NULL entry is left out, so {0,0,0,e3,e4} brackets the attend kernel
+ * alone.  The array is read at each scalekv_step call and must stay valid until
  * it is replaced or cleared. */
 scalekv_status scalekv_step_stage_events(void** events);
 

@@ -314,7 +314,7 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
   hipStream_t st = static_cast<hipStream_t>(stream);
   void** ev = g_stage_events;
   auto mark = [&](int i) -> hipError_t {
-    return ev ? hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) : hipSuccess;
+    return ev && ev[i] ? hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) : hipSuccess;
   };
   const int U = shape->n_seq * shape->n_head;
   const int32_t* idx = nullptr;  // identity unless a ranking is needed
