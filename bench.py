@@ -30,6 +30,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch of the pipelined attention kernel at 16 x 16 units, d128, bf16, keyed by
+# (n_cur, keep): rocprofv3 --pmc FETCH_SIZE (KiB, scaled by 2.0: what the same counter reads
+# for a plain copy of known size) plus --pmc WRITE_SIZE (KiB, scale 1.0), three launches
+# each.  The commands and the full per-kernel table are in profiles/step_hbm_traffic.md.
+ATTEND_PIPE_TRAFFIC = {
+    (144, 46): 44.0e6, (144, 9): 39.2e6,
+    (256, 82): 78.1e6, (256, 16): 69.5e6,
+    (400, 146): 124.2e6, (400, 29): 108.9e6,
+    (576, 246): 188.2e6, (576, 49): 160.5e6,
+    (1024, 390): 319.8e6, (1024, 78): 278.9e6,
+    (1600, 646): 582.5e6, (1600, 129): 466.6e6,
+    (2304, 1046): 932.8e6, (2304, 209): 744.5e6,
+    (4096, 1622): 1286.6e6, (4096, 324): 1116.4e6,
+}
+
 
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -214,7 +229,8 @@ def main() -> int:
     ms_per_step = wall * 1e3 / args.steps
     log(f"timed {args.steps} steps: {ms_per_step:.2f} ms per step")
 
-    attend_big = dict(ms=0.0, flops=0.0, launches=0)
+    attend_big = dict(ms=0.0, flops=0.0, launches=0, traffic=0.0, min_bytes=0.0)
+    traffic_known = (S, H, d) == (16, 16, 128)
     for s in range(args.steps):
         for i, (l, k, cache_len, keep, n_cur) in enumerate(meta):
             ev = ev_steps[s][i]
@@ -223,12 +239,18 @@ def main() -> int:
             attend_big["ms"] += events.elapsed_ms(ev[3], ev[4])
             attend_big["flops"] += 4.0 * n_cur * (keep + n_cur) * d * U
             attend_big["launches"] += 1
+            attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * (keep + n_cur)) * d * e * U
+            if traffic_known and (n_cur, keep) in ATTEND_PIPE_TRAFFIC:
+                attend_big["traffic"] += ATTEND_PIPE_TRAFFIC[(n_cur, keep)]
+            else:
+                traffic_known = False
 
     # ---- one more pass, outside the timed region, with an event at every stage boundary:
     # per-stage and per-scale times and the bandwidth of the two streaming stages
     stage_names = ("score", "select", "compact", "attend")
     stage_ms = {n: 0.0 for n in stage_names}
     per_scale_ms = {k: 0.0 for k in range(1, K + 1)}
+    per_scale_stage_ms = {k: [0.0] * 4 for k in range(1, K + 1)}
     attend_all = dict(ms=0.0, flops=0.0)
     compact_stat = dict(ms=0.0, bytes=0.0)
     score_stat = dict(ms=0.0, bytes=0.0)
@@ -244,8 +266,9 @@ def main() -> int:
         for i, (l, k, cache_len, keep, n_cur) in enumerate(meta):
             ev = ev_all[i]
             t = [events.elapsed_ms(ev[j], ev[j + 1]) for j in range(4)]
-            for n, x in zip(stage_names, t):
+            for j, (n, x) in enumerate(zip(stage_names, t)):
                 stage_ms[n] += x
+                per_scale_stage_ms[k][j] += x
             per_scale_ms[k] += sum(t)
             attend_all["ms"] += t[3]; attend_all["flops"] += 4.0 * n_cur * (keep + n_cur) * d * U
             compact_stat["ms"] += t[2]
@@ -261,7 +284,10 @@ def main() -> int:
     roofline = {
         "bound": "mfma", "kernel": "attend_pipe_kernel",
         "achieved": achieved_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+        "frac": achieved_tflops / PEAK_BF16_TFLOPS,
+        "traffic": dom["traffic"] / dom["launches"] if traffic_known and dom["launches"] else None,
+        "traffic_unit": "bytes per launch, mean over the timed launches (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
+        "algorithmic_bytes_per_launch": dom["min_bytes"] / max(1, dom["launches"]),
         "launches": dom["launches"], "avg_launch_ms": dom["ms"] / max(1, dom["launches"]),
         "flops_per_launch_avg": dom["flops"] / max(1, dom["launches"]),
     }
@@ -282,7 +308,8 @@ def main() -> int:
         "roofline": roofline,
         "stage_pass": None if ms_stage_pass is None else {
             "note": "one extra pass outside the timed region with an event at every stage boundary",
-            "ms": ms_stage_pass, "stage_ms": stage_ms, "per_scale_ms": per_scale_ms},
+            "ms": ms_stage_pass, "stage_ms": stage_ms, "per_scale_ms": per_scale_ms,
+            "per_scale_stage_ms": {str(k): [round(x, 4) for x in v] for k, v in per_scale_stage_ms.items()}},
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS},
         "score_hbm": {"achieved": score_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": score_gbs / PEAK_HBM_GBS},
