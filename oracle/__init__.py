@@ -1,4 +1,4 @@
-"""Python face of the fp64 CPU oracle (oracle/scalekv_oracle.c).
+"""Python face of the fp64 CPU oracle (oracle/scalekv_oracle.c, oracle/selection_literal.c).
 
 TEST INFRASTRUCTURE.  Only tests/, __graft_entry__.smoke() and bench.py's
 cpu_baseline leg may import this package.  It never imports the HIP binding and
@@ -31,6 +31,9 @@ def lib() -> ctypes.CDLL:
         _lib.scalekv_oracle_num_threads.restype = ctypes.c_int
         _lib.scalekv_oracle_cache_lengths.restype = ctypes.c_int
         _lib.scalekv_oracle_select.restype = ctypes.c_int
+        _lib.scalekv_oracle_window_centroids.restype = ctypes.c_int
+        _lib.scalekv_oracle_select_forced.restype = ctypes.c_int
+        _lib.scalekv_oracle_step_append_first_batch.restype = ctypes.c_int
     return _lib
 
 
@@ -143,3 +146,64 @@ def cache_lengths(prefix: int, n_tok: Sequence[int], budget: Sequence[int]) -> T
     li = np.zeros(K, dtype=np.int32); kp = np.zeros(K, dtype=np.int32)
     final = lib().scalekv_oracle_cache_lengths(int(prefix), _ip(n_tok), _ip(budget), K, _ip(li), _ip(kp))
     return li, kp, int(final)
+
+
+# ---- the literal reading of Sec. 3.3 (oracle/selection_literal.c)
+
+def window_centroids(h: int, w: int, ph: int = 4, pw: int = 4) -> np.ndarray:
+    """Raster indices of the centroid token of each patch of a ph x pw grid laid
+    over an h x w token map (Sec. 3.3, observation window)."""
+    idx = np.zeros(max(1, min(ph, h) * min(pw, w)), dtype=np.int32)
+    n = lib().scalekv_oracle_window_centroids(int(h), int(w), int(ph), int(pw), _ip(idx))
+    return idx[:n].copy()
+
+
+def pool(scores, pool_w: int) -> np.ndarray:
+    """Average pooling along the cache axis, odd width, zero padding. [U, len] -> [U, len]."""
+    scores = _f64(scores)
+    out = np.zeros_like(scores)
+    for u in range(scores.shape[0]):
+        lib().scalekv_oracle_pool(_dp(scores[u]), scores.shape[1], int(pool_w), _dp(out[u]))
+    return out
+
+
+def select_forced(scores, budget: int, forced: Sequence[int]) -> np.ndarray:
+    """Forced positions plus the top-min(budget, rest) of the others, ascending.
+    scores [U, len] -> idx [U, keep]."""
+    scores = _f64(scores)
+    U, L = scores.shape
+    f = np.ascontiguousarray(np.asarray(list(forced), dtype=np.int32))
+    buf = np.zeros((U, max(L, 1)), dtype=np.int32)
+    keep = None
+    for u in range(U):
+        got = lib().scalekv_oracle_select_forced(_dp(scores[u]), L, int(budget), _ip(f), len(f), _ip(buf[u]))
+        assert keep is None or got == keep
+        keep = got
+    return buf[:, :keep or 0].copy()
+
+
+def step_append_first(q, k_cur, v_cur, win_idx: Sequence[int], k_cache, v_cache, budget: int,
+                      pool_w: int = 1, scale: Optional[float] = None, force_idx=None):
+    """One (layer, scale) call in the order of Sec. 3.3: append -> attend ->
+    score over history and current map -> pool -> keep window + top-budget.
+    Returns dict(out [U, n_cur, d], scores [U, len], idx [U, keep],
+    k_next, v_next [U, keep, d], keep) with len = cache_len + n_cur."""
+    q, k_cur, v_cur, k_cache, v_cache = map(_f64, (q, k_cur, v_cur, k_cache, v_cache))
+    U, n_cur, d = q.shape
+    L = k_cache.shape[1]
+    n = L + n_cur
+    scale = default_scale(d) if scale is None else float(scale)
+    win = np.ascontiguousarray(np.asarray(list(win_idx), dtype=np.int32))
+    fidx, fkeep = None, 0
+    if force_idx is not None:
+        fidx = np.ascontiguousarray(np.asarray(force_idx, dtype=np.int32))
+        fkeep = fidx.shape[1]
+    k_next = np.zeros((U, n, d)); v_next = np.zeros((U, n, d))
+    idx = np.zeros((U, n), dtype=np.int32)
+    sc = np.zeros((U, n)); out = np.zeros((U, n_cur, d))
+    keep = lib().scalekv_oracle_step_append_first_batch(
+        U, _dp(q), _dp(k_cur), _dp(v_cur), n_cur, _ip(win), len(win), int(pool_w), _dp(k_cache),
+        _dp(v_cache), L, int(budget), d, ctypes.c_double(scale), _ip(fidx), fkeep, _dp(k_next),
+        _dp(v_next), _ip(idx), _dp(sc), _dp(out))
+    return dict(out=out, scores=sc, idx=idx[:, :keep].copy(), k_next=k_next[:, :keep].copy(),
+                v_next=v_next[:, :keep].copy(), keep=int(keep))
