@@ -51,6 +51,7 @@ extern "C" {
 #endif
 
 #define SCALEKV_MAX_WINDOW 16
+#define SCALEKV_MAX_POOL 31
 
 typedef enum {
   SCALEKV_OK = 0,
@@ -137,6 +138,69 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                             int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
                             const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
                             int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- Sec. 3.3 read literally: the map's K/V join the cache, the map attends, and only
+ * then is the cache pruned, with the observation window preserved. ---- */
+
+/* Observation window of Sec. 3.3 ("partition the map into N patches and select the
+ * centroid token from each patch").  Host only, no GPU work.  The map has map_h rows and
+ * map_w columns in raster order and is cut into a grid of gr x gc patches, gr =
+ * min(patch_rows, map_h), gc = min(patch_cols, map_w); band a of the rows covers rows
+ * [floor(a*map_h/gr), floor((a+1)*map_h/gr)), likewise the columns.  The centroid of a
+ * patch is the token nearest to the patch's centre; of equally near tokens the one with
+ * the smaller row, then the smaller column.  idx_out (host, at least gr*gc entries)
+ * receives the raster indices in ascending order, *n_out their number.
+ * Errors: non-positive sizes or NULL outputs -> INVALID_ARG. */
+scalekv_status scalekv_window_centroids(int32_t map_h, int32_t map_w, int32_t patch_rows,
+                                        int32_t patch_cols, int32_t* idx_out, int32_t* n_out);
+
+/* Selection of Sec. 3.3 with its two optional parts: average pooling of the scores
+ * ("we aggregate these scores through average pooling") and preserved positions ("these
+ * selected tokens, along with the observation window tokens, are preserved").
+ *   log_scores [S,H,cache_len] fp32 device: log of the importance scores (scalekv_score).
+ *   pool_w: odd, 1..SCALEKV_MAX_POOL.  The scores are averaged along the cache axis over
+ *     pool_w positions centred on each token, zeros beyond both ends, before ranking
+ *     (computed on the log-scores as a log-sum-exp; 1 = no pooling).
+ *   forced: host array of n_forced (0..SCALEKV_MAX_WINDOW) distinct positions in
+ *     [0, cache_len), the same for every unit; they are kept whatever their score and take
+ *     no part in the ranking.
+ *   Of the other cache_len - n_forced tokens the min(budget, cache_len - n_forced) with
+ *   the highest pooled score are selected, equal scores to the lower index.
+ *   idx [S,H,keep] int32 device receives the union, ascending; *keep_out (host, may be
+ *   NULL) = n_forced + min(budget, cache_len - n_forced), valid on return.
+ * Errors: as scalekv_select; pool_w even or out of range, a forced position out of range
+ * or repeated -> INVALID_ARG. */
+scalekv_status scalekv_select_window(const scalekv_shape* shape, const float* log_scores,
+                                     int32_t cache_len, int32_t budget, const int32_t* forced,
+                                     int32_t n_forced, int32_t pool_w, int32_t* idx,
+                                     int32_t* keep_out, void* stream);
+
+/* One (layer, scale) call in the order of Sec. 3.3, enqueued on `stream`:
+ *   1. rows [cache_len, cache_len + n_cur) of k_cache/v_cache <- k_cur/v_cur (in place;
+ *      the caches must have capacity for them),
+ *   2. out <- attention of q over all cache_len + n_cur rows, no mask,
+ *   3. importance scores (Eq. 5) of every row from the window queries, rows win_idx[0..n_win)
+ *      of q, each window row normalised over all cache_len + n_cur keys; pooled with pool_w,
+ *   4. the window tokens (cache positions cache_len + win_idx[j]) and the top-`budget` of
+ *      the other rows are kept,
+ *   5. k_next/v_next rows [0, keep) <- the kept rows, ascending.
+ * keep = n_win + min(budget, cache_len + n_cur - n_win), in *keep_out (host, may be NULL).
+ * If keep == cache_len + n_cur nothing is dropped: steps 3-5 are skipped, the cache stays
+ * in k_cache/v_cache (now cache_len + n_cur rows), k_next/v_next are not touched (may be
+ * NULL) and *moved_out (host, may be NULL) is 0; otherwise *moved_out is 1.
+ * idx_out (device, [S,H,keep], may be NULL) receives the kept positions.
+ * Workspace: scalekv_workspace_bytes(shape, cache_len + n_cur, n_cur).
+ * Errors: as scalekv_step, with cache_len + n_cur in place of cache_len for capacities;
+ * a ranking with n_win = 0 -> INVALID_ARG. */
+scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void* q,
+                                         const void* k_cur, const void* v_cur, int32_t n_cur,
+                                         const int32_t* win_idx, int32_t n_win, int32_t pool_w,
+                                         const scalekv_kv* k_cache, const scalekv_kv* v_cache,
+                                         int32_t cache_len, int32_t budget,
+                                         const scalekv_kv* k_next, const scalekv_kv* v_next,
+                                         int32_t* keep_out, int32_t* moved_out, void* out,
+                                         int32_t* idx_out, void* ws, size_t ws_bytes,
+                                         void* stream);
 
 /* Benchmark aid, not part of the method.  events: host array of 5 hipEvent_t
  * (created by the caller with timing enabled), or NULL to switch off.  While

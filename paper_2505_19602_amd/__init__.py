@@ -20,6 +20,10 @@ from .binding import (  # noqa: F401
     step,
     PreparedStep,
     step_stage_events,
+    window_centroids,
+    select_window,
+    step_append_first,
     MAX_WINDOW,
+    MAX_POOL,
     EXPORTED_SYMBOLS,
 )

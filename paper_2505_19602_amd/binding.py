@@ -17,11 +17,15 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 MAX_WINDOW = 16
 
-EXPORTED_SYMBOLS = (
+MAX_POOL = 31
+
+# status-returning entry points first, then the two that return strings
+_STATUS_SYMBOLS = (
     "scalekv_workspace_bytes", "scalekv_score", "scalekv_select", "scalekv_compact",
-    "scalekv_attend", "scalekv_step", "scalekv_step_stage_events", "scalekv_last_error",
-    "scalekv_version",
+    "scalekv_attend", "scalekv_step", "scalekv_step_stage_events",
+    "scalekv_window_centroids", "scalekv_select_window", "scalekv_step_append_first",
 )
+EXPORTED_SYMBOLS = _STATUS_SYMBOLS + ("scalekv_last_error", "scalekv_version")
 
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE", 4: "HIP"}
 
@@ -77,7 +81,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(path)
         L.scalekv_last_error.restype = ctypes.c_char_p
         L.scalekv_version.restype = ctypes.c_char_p
-        for name in EXPORTED_SYMBOLS[:7]:
+        for name in _STATUS_SYMBOLS:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -272,3 +276,67 @@ def step_stage_events(events) -> None:
     """scalekv_step_stage_events: `events` is a ctypes array of 5 hipEvent_t
     (c_void_p) or None."""
     _check(lib().scalekv_step_stage_events(events))
+
+
+# ---- Sec. 3.3 read literally: append, attend, then prune with the window preserved
+
+def window_centroids(map_h: int, map_w: int, patch_rows: int = 4, patch_cols: int = 4) -> list:
+    """scalekv_window_centroids: raster indices of the centroid token of each patch."""
+    cap = max(1, min(int(patch_rows), int(map_h)) * min(int(patch_cols), int(map_w)))
+    buf = (ctypes.c_int32 * cap)()
+    n = ctypes.c_int32(0)
+    _check(lib().scalekv_window_centroids(int(map_h), int(map_w), int(patch_rows), int(patch_cols), buf,
+                                          ctypes.byref(n)))
+    return [int(buf[i]) for i in range(n.value)]
+
+
+def _idx_tensor(t: Optional[torch.Tensor], shape: Shape, keep: int, name: str) -> None:
+    if t is None:
+        return
+    if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() \
+            or tuple(t.shape) != (shape.n_seq, shape.n_head, keep):
+        raise ScaleKVError(1, f"{name} must be a contiguous int32 device tensor [S,H,{keep}]")
+
+
+def select_window(shape: Shape, log_scores: torch.Tensor, cache_len: int, budget: int,
+                  forced: Sequence[int], pool_w: int, idx: torch.Tensor) -> int:
+    """scalekv_select_window: forced positions + top-budget of the rest by pooled score; returns keep."""
+    if log_scores.dtype != torch.float32 or not log_scores.is_cuda or not log_scores.is_contiguous() \
+            or tuple(log_scores.shape) != (shape.n_seq, shape.n_head, cache_len):
+        raise ScaleKVError(1, "log_scores must be a contiguous fp32 device tensor [S,H,cache_len]")
+    keep = len(forced) + max(0, min(int(budget), int(cache_len) - len(forced)))
+    _idx_tensor(idx, shape, keep, "idx")
+    f = (ctypes.c_int32 * max(1, len(forced)))(*[int(x) for x in forced])
+    cs = shape.c()
+    out = ctypes.c_int32(-1)
+    _check(lib().scalekv_select_window(ctypes.byref(cs), _ptr(log_scores), int(cache_len), int(budget), f,
+                                       int(len(forced)), int(pool_w), _ptr(idx), ctypes.byref(out), _stream()))
+    return int(out.value)
+
+
+def step_append_first(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor,
+                      win_idx: Sequence[int], pool_w: int, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                      cache_len: int, budget: int, k_next: Optional[torch.Tensor],
+                      v_next: Optional[torch.Tensor], out: torch.Tensor, idx_out: Optional[torch.Tensor],
+                      ws: Optional[torch.Tensor]):
+    """scalekv_step_append_first; returns (keep, moved): the next cache has `keep` rows and
+    lives in k_next/v_next if `moved`, else still in k_cache/v_cache."""
+    n_cur = q.shape[2]
+    _dense(q, shape, n_cur, "q"); _dense(k_cur, shape, n_cur, "k_cur"); _dense(v_cur, shape, n_cur, "v_cur")
+    _dense(out, shape, n_cur, "out")
+    total = int(cache_len) + n_cur
+    keep = len(win_idx) + max(0, min(int(budget), total - len(win_idx)))
+    _idx_tensor(idx_out, shape, keep, "idx_out")
+    win = (ctypes.c_int32 * max(1, len(win_idx)))(*[int(w) for w in win_idx])
+    cs = shape.c()
+    a, b = _kv(k_cache, shape, "k_cache"), _kv(v_cache, shape, "v_cache")
+    c = _kv(k_next, shape, "k_next") if k_next is not None else None
+    d = _kv(v_next, shape, "v_next") if v_next is not None else None
+    wp, wb = _ws(ws)
+    keep_out, moved = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    _check(lib().scalekv_step_append_first(
+        ctypes.byref(cs), _ptr(q), _ptr(k_cur), _ptr(v_cur), int(n_cur), win, int(len(win_idx)), int(pool_w),
+        ctypes.byref(a), ctypes.byref(b), int(cache_len), int(budget),
+        ctypes.byref(c) if c is not None else None, ctypes.byref(d) if d is not None else None,
+        ctypes.byref(keep_out), ctypes.byref(moved), _ptr(out), _ptr(idx_out), wp, wb, _stream()))
+    return int(keep_out.value), bool(moved.value)

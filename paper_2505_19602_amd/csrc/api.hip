@@ -147,6 +147,31 @@ ScoreWorkspace score_ws(const WsLayout& w, void* ws) {
   return sw;
 }
 
+// forced positions and pooling width of the selection -> SelectExtras, validated
+scalekv_status make_extras(const int32_t* forced, int n_forced, int pool_w, int cache_len,
+                           SelectExtras* ex) {
+  if (n_forced < 0 || n_forced > SCALEKV_MAX_WINDOW)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_forced %d is outside 0..%d", n_forced,
+                SCALEKV_MAX_WINDOW);
+  if (n_forced > 0 && !forced) return fail(SCALEKV_ERR_INVALID_ARG, "forced is NULL");
+  if (pool_w < 1 || pool_w % 2 == 0 || pool_w > SCALEKV_MAX_POOL)
+    return fail(SCALEKV_ERR_INVALID_ARG, "pool_w %d must be odd and in 1..%d", pool_w,
+                SCALEKV_MAX_POOL);
+  ex->n_forced = n_forced;
+  ex->pool_w = pool_w;
+  for (int j = 0; j < kMaxWindow; ++j) ex->forced[j] = 0;
+  for (int j = 0; j < n_forced; ++j) {
+    if (forced[j] < 0 || forced[j] >= cache_len)
+      return fail(SCALEKV_ERR_INVALID_ARG, "forced[%d] = %d is outside 0..cache_len-1", j,
+                  forced[j]);
+    for (int i = 0; i < j; ++i)
+      if (forced[i] == forced[j])
+        return fail(SCALEKV_ERR_INVALID_ARG, "forced[%d] repeats position %d", j, forced[j]);
+    ex->forced[j] = forced[j];
+  }
+  return SCALEKV_OK;
+}
+
 #define SCALEKV_TRY(expr)                       \
   do {                                          \
     scalekv_status _st = (expr);                \
@@ -221,7 +246,7 @@ scalekv_status scalekv_select(const scalekv_shape* shape, const float* scores, i
   }
   if (keep_out) *keep_out = keep;
   SCALEKV_HIP(launch_select(shape->n_seq * shape->n_head, scores, cache_len, cache_len, keep, idx,
-                            static_cast<hipStream_t>(stream)),
+                            nullptr, static_cast<hipStream_t>(stream)),
               "select launch");
   return SCALEKV_OK;
 }
@@ -334,11 +359,12 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
     SCALEKV_HIP(mark(1), "event record");
     // the finalisation of the score is fused into the select; very long caches take the
     // two-kernel route through the scores buffer
-    hipError_t fused = launch_select_from_logits(U, n_win, sw, cache_len, keep, idx_ws, st);
+    hipError_t fused = launch_select_from_logits(U, n_win, sw, cache_len, keep, idx_ws, nullptr, st);
     if (fused == hipErrorNotSupported) {
       SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
                   "score finalize launch");
-      SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, st), "select launch");
+      SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, nullptr, st),
+                  "select launch");
     } else {
       SCALEKV_HIP(fused, "fused select launch");
     }
@@ -346,7 +372,8 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
   } else {
     SCALEKV_HIP(mark(1), "event record");
     if (idx_out && keep > 0)  // keep == cache_len: the selection is the identity
-      SCALEKV_HIP(launch_select(U, nullptr, 0, cache_len, keep, idx_out, st), "select launch");
+      SCALEKV_HIP(launch_select(U, nullptr, 0, cache_len, keep, idx_out, nullptr, st),
+                  "select launch");
   }
   SCALEKV_HIP(mark(2), "event record");
   SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
@@ -359,6 +386,164 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
               "attend launch");
   SCALEKV_HIP(mark(4), "event record");
   if (new_len_out) *new_len_out = keep + n_cur;
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_window_centroids(int32_t map_h, int32_t map_w, int32_t patch_rows,
+                                        int32_t patch_cols, int32_t* idx_out, int32_t* n_out) {
+  if (map_h < 1 || map_w < 1 || patch_rows < 1 || patch_cols < 1)
+    return fail(SCALEKV_ERR_INVALID_ARG, "map %dx%d and patch grid %dx%d must be positive", map_h,
+                map_w, patch_rows, patch_cols);
+  if ((long long)map_h * map_w > 0x7fffffffLL)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "map %dx%d has too many tokens", map_h, map_w);
+  if (!idx_out || !n_out) return fail(SCALEKV_ERR_INVALID_ARG, "idx_out or n_out is NULL");
+  const int gr = patch_rows < map_h ? patch_rows : map_h;
+  const int gc = patch_cols < map_w ? patch_cols : map_w;
+  // Band a of gr covers rows [a*h/gr, (a+1)*h/gr).  The token nearest to the middle of a band
+  // [lo, hi) is row (lo + hi - 1) / 2: for an even band the two middle rows are equally near
+  // and the lower one is taken.  Rows and columns are independent, so the centroid of a patch
+  // is (middle row of its row band, middle column of its column band).
+  int n = 0;
+  for (int a = 0; a < gr; ++a) {
+    const int r_lo = (int)((long long)a * map_h / gr), r_hi = (int)((long long)(a + 1) * map_h / gr);
+    const int r = (r_lo + r_hi - 1) / 2;
+    for (int b = 0; b < gc; ++b) {
+      const int c_lo = (int)((long long)b * map_w / gc), c_hi = (int)((long long)(b + 1) * map_w / gc);
+      idx_out[n++] = r * map_w + (c_lo + c_hi - 1) / 2;
+    }
+  }
+  *n_out = n;
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_select_window(const scalekv_shape* shape, const float* log_scores,
+                                     int32_t cache_len, int32_t budget, const int32_t* forced,
+                                     int32_t n_forced, int32_t pool_w, int32_t* idx,
+                                     int32_t* keep_out, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  if (budget < 0) return fail(SCALEKV_ERR_INVALID_ARG, "budget is negative (%d)", budget);
+  SelectExtras ex;
+  SCALEKV_TRY(make_extras(forced, n_forced, pool_w, cache_len, &ex));
+  const int rest = cache_len - n_forced;
+  const int keep = n_forced + (budget < rest ? budget : rest);
+  if (keep > 0) {
+    if (!log_scores) return fail(SCALEKV_ERR_INVALID_ARG, "log_scores is NULL");
+    if (!idx) return fail(SCALEKV_ERR_INVALID_ARG, "idx is NULL");
+  }
+  if (keep_out) *keep_out = keep;
+  SCALEKV_HIP(launch_select(shape->n_seq * shape->n_head, log_scores, cache_len, cache_len, keep,
+                            idx, &ex, static_cast<hipStream_t>(stream)),
+              "select launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void* q,
+                                         const void* k_cur, const void* v_cur, int32_t n_cur,
+                                         const int32_t* win_idx, int32_t n_win, int32_t pool_w,
+                                         const scalekv_kv* k_cache, const scalekv_kv* v_cache,
+                                         int32_t cache_len, int32_t budget,
+                                         const scalekv_kv* k_next, const scalekv_kv* v_next,
+                                         int32_t* keep_out, int32_t* moved_out, void* out,
+                                         int32_t* idx_out, void* ws, size_t ws_bytes,
+                                         void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  if (n_cur < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_cur must be >= 1 (got %d)", n_cur);
+  SCALEKV_TRY(check_rows(shape, n_cur, "n_cur"));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  const long long len_ll = (long long)cache_len + n_cur;
+  SCALEKV_TRY(check_rows(shape, len_ll, "cache_len + n_cur"));
+  const int len = (int)len_ll;
+  if (budget < 0) return fail(SCALEKV_ERR_INVALID_ARG, "budget is negative (%d)", budget);
+  if (n_win < 0 || n_win > SCALEKV_MAX_WINDOW)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_win %d is outside 0..%d", n_win, SCALEKV_MAX_WINDOW);
+  if (n_win > n_cur) return fail(SCALEKV_ERR_INVALID_ARG, "n_win %d exceeds n_cur %d", n_win, n_cur);
+  if (n_win > 0 && !win_idx) return fail(SCALEKV_ERR_INVALID_ARG, "win_idx is NULL");
+  int32_t forced[kMaxWindow];
+  for (int j = 0; j < n_win; ++j) {
+    if (win_idx[j] < 0 || win_idx[j] >= n_cur)
+      return fail(SCALEKV_ERR_INVALID_ARG, "win_idx[%d] = %d is outside 0..n_cur-1", j, win_idx[j]);
+    forced[j] = cache_len + win_idx[j];
+  }
+  SelectExtras ex;
+  SCALEKV_TRY(make_extras(forced, n_win, pool_w, len, &ex));
+  const int rest = len - n_win;
+  const int keep = n_win + (budget < rest ? budget : rest);
+  const bool moves = keep < len;            // otherwise everything is kept
+  const bool ranks = moves && keep > 0;
+  if (ranks && n_win < 1)
+    return fail(SCALEKV_ERR_INVALID_ARG, "a ranking is needed but the window is empty");
+  if (ranks) SCALEKV_TRY(check_ws(shape, len, ws, ws_bytes));
+  SCALEKV_TRY(check_dense(q, true, "q"));
+  SCALEKV_TRY(check_dense(k_cur, true, "k_cur"));
+  SCALEKV_TRY(check_dense(v_cur, true, "v_cur"));
+  SCALEKV_TRY(check_dense(out, true, "out"));
+  SCALEKV_TRY(check_kv(shape, k_cache, len, "k_cache"));
+  SCALEKV_TRY(check_kv(shape, v_cache, len, "v_cache"));
+  if (overlaps(shape, k_cache, v_cache))
+    return fail(SCALEKV_ERR_INVALID_ARG, "k_cache and v_cache overlap");
+  if (moves) {
+    SCALEKV_TRY(check_kv(shape, k_next, keep, "k_next"));
+    SCALEKV_TRY(check_kv(shape, v_next, keep, "v_next"));
+    if (overlaps(shape, k_cache, k_next) || overlaps(shape, k_cache, v_next) ||
+        overlaps(shape, v_cache, k_next) || overlaps(shape, v_cache, v_next) ||
+        overlaps(shape, k_next, v_next))
+      return fail(SCALEKV_ERR_INVALID_ARG, "cache and next-cache buffers overlap");
+  }
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int U = shape->n_seq * shape->n_head;
+  const int d = shape->head_dim;
+  // 1. the map's K/V join the cache: rows [cache_len, cache_len + n_cur) of every unit
+  {
+    const long long tail = (long long)cache_len * d * elem_bytes(shape);
+    KvView kt{static_cast<const char*>(k_cache->ptr) + tail, k_cache->seq_stride,
+              k_cache->head_stride};
+    KvView vt{static_cast<const char*>(v_cache->ptr) + tail, v_cache->seq_stride,
+              v_cache->head_stride};
+    SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, d, view(k_cache),
+                               view(v_cache), nullptr, 0, k_cur, v_cur, n_cur, kt, vt, st),
+                "append launch");
+  }
+  // 2. the map attends over history and itself
+  SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, d, q, n_cur, view(k_cache),
+                            view(v_cache), len, resolve_scale(shape), out, st),
+              "attend launch");
+  if (keep_out) *keep_out = keep;
+  if (moved_out) *moved_out = moves ? 1 : 0;
+  if (!moves) {  // everything is kept: the cache stays where it is
+    if (idx_out)
+      SCALEKV_HIP(launch_select(U, nullptr, 0, len, len, idx_out, nullptr, st), "select launch");
+    return SCALEKV_OK;
+  }
+  // 3. scores of the window rows against the whole cache, pooled; window kept + top-budget
+  int32_t* idx_ws = idx_out;
+  if (!idx_ws && ranks)
+    idx_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + ws_layout(shape, len).idx_off);
+  if (ranks) {
+    const WsLayout w = ws_layout(shape, len);
+    const ScoreWorkspace sw = score_ws(w, ws);
+    float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + w.scores_off);
+    WindowRows rows;
+    for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
+    SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, d, q,
+                                    (long long)n_cur * d, rows, n_win, view(k_cache), len,
+                                    resolve_scale(shape), sw, st),
+                "score logits launch");
+    hipError_t fused = launch_select_from_logits(U, n_win, sw, len, keep, idx_ws, &ex, st);
+    if (fused == hipErrorNotSupported) {
+      SCALEKV_HIP(launch_score_finalize(U, n_win, len, sw, scores, w.len_pad, st),
+                  "score finalize launch");
+      SCALEKV_HIP(launch_select(U, scores, w.len_pad, len, keep, idx_ws, &ex, st), "select launch");
+    } else {
+      SCALEKV_HIP(fused, "fused select launch");
+    }
+  }
+  // 4. the kept rows become the next cache
+  SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, d, view(k_cache),
+                             view(v_cache), idx_ws, keep, nullptr, nullptr, 0, view(k_next),
+                             view(v_next), st),
+              "compact launch");
   return SCALEKV_OK;
 }
 

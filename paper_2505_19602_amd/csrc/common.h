@@ -27,6 +27,14 @@ struct ScoreWorkspace {
   int n_chunk;
 };
 
+// Optional parts of the selection (Sec. 3.3): positions preserved whatever their score
+// (the observation window) and average pooling of the scores along the cache axis.
+struct SelectExtras {
+  int n_forced;             // 0..kMaxWindow
+  int forced[kMaxWindow];   // distinct positions in [0, cache_len)
+  int pool_w;               // odd, 1 = no pooling
+};
+
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // ---- launchers (each enqueues on `stream` and returns hipGetLastError()) ----
@@ -38,12 +46,15 @@ hipError_t launch_score_logits(int dtype, int n_seq, int n_head, int d, const vo
 hipError_t launch_score_finalize(int n_unit, int n_win, int cache_len, ScoreWorkspace ws,
                                  float* log_scores, long long score_unit_stride,
                                  hipStream_t stream);
+// `keep` counts the forced positions of `extras` (NULL: none, no pooling) as well.
 hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
-                         int cache_len, int keep, int32_t* idx, hipStream_t stream);
+                         int cache_len, int keep, int32_t* idx, const SelectExtras* extras,
+                         hipStream_t stream);
 // select straight from the logits workspace (score finalisation fused in); returns
 // hipErrorNotSupported when the unit is too long for the fused kernel
 hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
-                                     int keep, int32_t* idx, hipStream_t stream);
+                                     int keep, int32_t* idx, const SelectExtras* extras,
+                                     hipStream_t stream);
 hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src, KvView v_src,
                           const int32_t* idx, int keep, const void* k_cur, const void* v_cur,
                           int n_cur, KvView k_dst, KvView v_dst, hipStream_t stream);

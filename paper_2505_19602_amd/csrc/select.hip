@@ -5,6 +5,12 @@
 // emits, in ascending index order, every index with key > T and the first
 // (keep - #greater) indices with key == T.  Only integer compares are involved,
 // so the result is deterministic and ties always go to the lower index.
+//
+// Two optional parts of the paper's selection are folded into the key set-up:
+// average pooling of the scores along the cache axis (odd width, zeros beyond the
+// ends; done on log-scores as a log-sum-exp, which ranks the same), and positions
+// that are preserved whatever their score (the observation window): those get the
+// largest key, and `keep` counts them.
 #include "common.h"
 
 namespace scalekv {
@@ -21,13 +27,27 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 
 // FUSED: the scores are not read but formed here from the logits workspace (the score
 // finalisation), so the fused step neither writes nor re-reads them.
+// log of the average of exp(v[i + t]), |t| <= r, positions outside [0, len) counting as zero
+template <typename Load>
+__device__ __forceinline__ float pooled_log(Load v, int i, int len, int r) {
+  const int a = max(i - r, 0), b = min(i + r, len - 1);
+  float m = -INFINITY;
+  for (int t = a; t <= b; ++t) m = fmaxf(m, v(t));
+  if (!(m > -INFINITY)) return -INFINITY;
+  float acc = 0.f;
+  for (int t = a; t <= b; ++t) acc += expf(v(t) - m);
+  return m + logf(acc) - logf((float)(2 * r + 1));
+}
+
 template <bool IN_LDS, bool FUSED>
 __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
                                                           long long score_unit_stride,
                                                           int cache_len, int keep,
                                                           int32_t* __restrict__ idx,
-                                                          ScoreWorkspace ws, int n_win) {
+                                                          ScoreWorkspace ws, int n_win,
+                                                          SelectExtras ex) {
   static_assert(IN_LDS || !FUSED, "the fused form keeps its keys in LDS");
+  constexpr int kPerThread = IN_LDS ? kLdsKeys / kThreads : 1;
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
   __shared__ float row_shift[kMaxWindow];
   __shared__ uint32_t hist[256];
@@ -37,17 +57,47 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   const int unit = blockIdx.x;
   const int tid = threadIdx.x;
   const float* s = scores + unit * score_unit_stride;
+  const int pool_r = (ex.pool_w - 1) / 2;
   auto key_at = [&](int i) -> uint32_t {
-    if constexpr (IN_LDS) return keys[i];
-    else return order_key(s[i]);
+    if constexpr (IN_LDS) {
+      return keys[i];
+    } else {
+      for (int j = 0; j < ex.n_forced; ++j)
+        if (ex.forced[j] == i) return 0xffffffffu;
+      if (pool_r > 0) return order_key(pooled_log([&](int t) { return s[t]; }, i, cache_len, pool_r));
+      return order_key(s[i]);
+    }
   };
-  if constexpr (FUSED) {
-    if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
+  if constexpr (IN_LDS) {
+    // log-scores into LDS (formed from the logits workspace when FUSED), pooled in place if
+    // asked for, then turned into keys
+    if constexpr (FUSED) {
+      if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
+      __syncthreads();
+    }
+    float* raw = reinterpret_cast<float*>(keys);
+    for (int i = tid; i < cache_len; i += kThreads) {
+      if constexpr (FUSED) raw[i] = score_log_sum(ws, unit, i, n_win, row_shift);
+      else raw[i] = s[i];
+    }
     __syncthreads();
-    for (int i = tid; i < cache_len; i += kThreads)
-      keys[i] = order_key(score_log_sum(ws, unit, i, n_win, row_shift));
-  } else if constexpr (IN_LDS) {
-    for (int i = tid; i < cache_len; i += kThreads) keys[i] = order_key(s[i]);
+    float mine[kPerThread];
+#pragma unroll
+    for (int c = 0; c < kPerThread; ++c) {
+      const int i = tid + c * kThreads;
+      if (i < cache_len)
+        mine[c] = pool_r > 0 ? pooled_log([&](int t) { return raw[t]; }, i, cache_len, pool_r) : raw[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kPerThread; ++c) {
+      const int i = tid + c * kThreads;
+      if (i < cache_len) keys[i] = order_key(mine[c]);
+    }
+    if (ex.n_forced > 0) {
+      __syncthreads();
+      if (tid < ex.n_forced) keys[ex.forced[tid]] = 0xffffffffu;
+    }
   }
 
   // ---- radix select: T = key of the keep-th largest ----
@@ -136,7 +186,11 @@ __global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total
 }  // namespace
 
 hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
-                         int cache_len, int keep, int32_t* idx, hipStream_t stream) {
+                         int cache_len, int keep, int32_t* idx, const SelectExtras* extras,
+                         hipStream_t stream) {
+  SelectExtras ex{};
+  ex.pool_w = 1;
+  if (extras) ex = *extras;
   if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
   if (keep >= cache_len) {  // keep everything: identity, no ranking needed
     const long long total = (long long)n_unit * keep;
@@ -147,19 +201,23 @@ hipError_t launch_select(int n_unit, const float* scores, long long score_unit_s
   const ScoreWorkspace none{nullptr, nullptr, 0, 0};
   if (cache_len <= kLdsKeys)
     hipLaunchKernelGGL((select_kernel<true, false>), dim3(n_unit), dim3(kThreads), 0, stream,
-                       scores, score_unit_stride, cache_len, keep, idx, none, 0);
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex);
   else
     hipLaunchKernelGGL((select_kernel<false, false>), dim3(n_unit), dim3(kThreads), 0, stream,
-                       scores, score_unit_stride, cache_len, keep, idx, none, 0);
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex);
   return hipGetLastError();
 }
 
 hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
-                                     int keep, int32_t* idx, hipStream_t stream) {
+                                     int keep, int32_t* idx, const SelectExtras* extras,
+                                     hipStream_t stream) {
+  SelectExtras ex{};
+  ex.pool_w = 1;
+  if (extras) ex = *extras;
   if (cache_len > kLdsKeys) return hipErrorNotSupported;
   if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
   hipLaunchKernelGGL((select_kernel<true, true>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
-                     0, cache_len, keep, idx, ws, n_win);
+                     0, cache_len, keep, idx, ws, n_win, ex);
   return hipGetLastError();
 }
 

@@ -152,3 +152,77 @@ def test_binding_rejects_wrong_tensors_before_calling_c():
         skv.attend(shape, q, q, q, 4, q)          # CPU tensors are not device memory
     with pytest.raises(skv.ScaleKVError):
         skv.Shape(1, 2, 128, torch.float16).c()
+
+
+# ---- entry points of the literal order of Sec. 3.3
+
+@pytest.mark.parametrize("h,w,ph,pw", [(1, 1, 4, 4), (2, 2, 4, 4), (4, 4, 4, 4), (6, 6, 4, 4), (8, 8, 4, 4),
+                                        (12, 12, 4, 4), (16, 16, 4, 4), (20, 20, 4, 4), (24, 24, 4, 4),
+                                        (32, 32, 4, 4), (40, 40, 4, 4), (48, 48, 4, 4), (64, 64, 4, 4),
+                                        (6, 10, 4, 4), (7, 5, 2, 3), (64, 64, 3, 5), (33, 17, 4, 4), (5, 64, 8, 8)])
+def test_window_centroids_match_the_oracle(L, h, w, ph, pw):
+    # host-only integer work: the library's result is compared with the oracle's on the CPU
+    import oracle
+    assert skv.window_centroids(h, w, ph, pw) == oracle.window_centroids(h, w, ph, pw).tolist()
+
+
+def test_window_centroids_argument_errors(L):
+    buf = (ctypes.c_int32 * 16)()
+    n = ctypes.c_int32(0)
+    assert L.scalekv_window_centroids(0, 4, 4, 4, buf, ctypes.byref(n)) == 1
+    assert L.scalekv_window_centroids(4, 4, 0, 4, buf, ctypes.byref(n)) == 1
+    assert L.scalekv_window_centroids(4, 4, 4, 4, None, ctypes.byref(n)) == 1
+    assert L.scalekv_window_centroids(4, 4, 4, 4, buf, None) == 1
+    assert L.scalekv_window_centroids(65536, 65536, 4, 4, buf, ctypes.byref(n)) == 2
+
+
+def test_select_window_argument_errors(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    keep = ctypes.c_int32(-5)
+    f = (ctypes.c_int32 * 3)(1, 4, 9)
+    call = lambda budget=3, forced=f, n_forced=3, pool_w=1, scores=p(0x1000), idx=p(0x2000), cache_len=10: \
+        L.scalekv_select_window(ctypes.byref(s), scores, cache_len, budget, forced, n_forced, pool_w, idx,
+                                ctypes.byref(keep), None)
+    assert call(budget=-1) == 1
+    assert call(pool_w=2) == 1 and "pool_w" in _err(L)
+    assert call(pool_w=0) == 1
+    assert call(pool_w=33) == 1
+    assert call(n_forced=17) == 1
+    assert call(forced=None) == 1
+    assert call(forced=(ctypes.c_int32 * 3)(1, 4, 10)) == 1 and "forced[2]" in _err(L)
+    assert call(forced=(ctypes.c_int32 * 3)(1, 4, 4)) == 1 and "repeats" in _err(L)
+    assert call(scores=p(0)) == 1
+    assert call(idx=p(0)) == 1
+    # nothing to select: legal no-op that needs no device
+    assert call(budget=0, n_forced=0, scores=p(0), idx=p(0)) == 0 and keep.value == 0
+
+
+def test_step_append_first_argument_errors(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    span = 64 * 128 * 2 * 2
+    k, v = _kv(0x100000), _kv(0x100000 + span)
+    kn, vn = _kv(0x100000 + 2 * span), _kv(0x100000 + 3 * span)
+    win = (ctypes.c_int32 * 4)(0, 1, 2, 9)
+    keep, moved = ctypes.c_int32(0), ctypes.c_int32(0)
+    big = ctypes.c_size_t(1 << 30)
+
+    def step(n_cur=16, n_win=4, pool_w=1, cache_len=40, budget=10, ws=p(0x8000), ws_bytes=big, w=win,
+             kc=k, vc=v, k_next=kn):
+        return L.scalekv_step_append_first(
+            ctypes.byref(s), p(0x1000), p(0x2000), p(0x3000), n_cur, w, n_win, pool_w, ctypes.byref(kc),
+            ctypes.byref(vc), cache_len, budget, ctypes.byref(k_next), ctypes.byref(vn), ctypes.byref(keep),
+            ctypes.byref(moved), p(0x4000), p(0), ws, ws_bytes, None)
+    assert step(n_cur=8) == 1 and "win_idx[3]" in _err(L)
+    assert step(n_cur=0) == 1
+    assert step(budget=-1) == 1
+    assert step(pool_w=4) == 1
+    assert step(n_win=17, n_cur=20) == 1
+    assert step(cache_len=50) == 1 and "capacity" in _err(L)      # 50 + 16 rows do not fit 64
+    assert step(ws=p(0)) == 3
+    assert step(ws_bytes=ctypes.c_size_t(8)) == 3
+    assert step(n_win=0) == 1 and "window" in _err(L)             # a ranking without window rows
+    assert step(vc=k) == 1 and "overlap" in _err(L)
+    assert step(k_next=k) == 1 and "overlap" in _err(L)
+    assert step(w=(ctypes.c_int32 * 4)(0, 1, 2, 2)) == 1 and "repeats" in _err(L)
