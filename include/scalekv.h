@@ -208,8 +208,10 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
  * before the first kernel and events[1..4] after the score, select, compact and
  * attend kernels respectively (stages that are skipped record their event
  * anyway).  A NULL entry is left out, so {0,0,0,e3,e4} brackets the attend kernel
- * alone.  The array is read at each scalekv_step call and must stay valid until
- * it is replaced or cleared. */
+ * alone.  scalekv_step_append_first records them too: events[0] before the first
+ * kernel, events[1..4] after its append, attend, score+select and compact kernels.
+ * The array is read at each such call and must stay valid until it is replaced or
+ * cleared. */
 scalekv_status scalekv_step_stage_events(void** events);
 
 /* Message for the calling thread's most recent non-OK status (static storage,

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     attend,
     step,
     PreparedStep,
+    PreparedAppendFirst,
     step_stage_events,
     window_centroids,
     select_window,

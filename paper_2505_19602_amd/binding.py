@@ -272,6 +272,47 @@ class PreparedStep:
         return self.new_len
 
 
+class PreparedAppendFirst:
+    """One scalekv_step_append_first call with every argument already marshalled (see
+    PreparedStep).  `keep` and `moved` are known on the host before anything runs."""
+
+    __slots__ = ("_args", "keep", "moved", "_refs", "_fn")
+
+    def __init__(self, shape: Shape, q, k_cur, v_cur, win_idx, pool_w, k_cache, v_cache, cache_len, budget,
+                 k_next, v_next, out, idx_out, ws):
+        n_cur = q.shape[2]
+        _dense(q, shape, n_cur, "q"); _dense(k_cur, shape, n_cur, "k_cur"); _dense(v_cur, shape, n_cur, "v_cur")
+        _dense(out, shape, n_cur, "out")
+        total = int(cache_len) + n_cur
+        self.keep = len(win_idx) + max(0, min(int(budget), total - len(win_idx)))
+        self.moved = self.keep < total
+        _idx_tensor(idx_out, shape, self.keep, "idx_out")
+        win = (ctypes.c_int32 * max(1, len(win_idx)))(*[int(w) for w in win_idx])
+        cs = shape.c()
+        a, b = _kv(k_cache, shape, "k_cache"), _kv(v_cache, shape, "v_cache")
+        c = _kv(k_next, shape, "k_next") if k_next is not None else None
+        d = _kv(v_next, shape, "v_next") if v_next is not None else None
+        wp, wb = _ws(ws)
+        keep_out, moved = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        self._refs = (cs, win, a, b, c, d, keep_out, moved, q, k_cur, v_cur, k_cache, v_cache, k_next, v_next, out,
+                      idx_out, ws)
+        self._args = [ctypes.byref(cs), _ptr(q), _ptr(k_cur), _ptr(v_cur), ctypes.c_int32(n_cur), win,
+                      ctypes.c_int32(len(win_idx)), ctypes.c_int32(pool_w), ctypes.byref(a), ctypes.byref(b),
+                      ctypes.c_int32(cache_len), ctypes.c_int32(budget),
+                      ctypes.byref(c) if c is not None else None, ctypes.byref(d) if d is not None else None,
+                      ctypes.byref(keep_out), ctypes.byref(moved), _ptr(out), _ptr(idx_out), wp, wb, None]
+        self._fn = lib().scalekv_step_append_first
+
+    def __call__(self, stream_ptr: Optional[int] = None) -> int:
+        args = self._args
+        args[-1] = ctypes.c_void_p(stream_ptr if stream_ptr is not None
+                                   else torch.cuda.current_stream().cuda_stream)
+        status = self._fn(*args)
+        if status != 0:
+            _check(status)
+        return self.keep
+
+
 def step_stage_events(events) -> None:
     """scalekv_step_stage_events: `events` is a ctypes array of 5 hipEvent_t
     (c_void_p) or None."""

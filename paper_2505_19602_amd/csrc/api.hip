@@ -492,8 +492,13 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
   }
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  void** ev = g_stage_events;
+  auto mark = [&](int i) -> hipError_t {
+    return ev && ev[i] ? hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) : hipSuccess;
+  };
   const int U = shape->n_seq * shape->n_head;
   const int d = shape->head_dim;
+  SCALEKV_HIP(mark(0), "event record");
   // 1. the map's K/V join the cache: rows [cache_len, cache_len + n_cur) of every unit
   {
     const long long tail = (long long)cache_len * d * elem_bytes(shape);
@@ -505,15 +510,19 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
                                view(v_cache), nullptr, 0, k_cur, v_cur, n_cur, kt, vt, st),
                 "append launch");
   }
+  SCALEKV_HIP(mark(1), "event record");
   // 2. the map attends over history and itself
   SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, d, q, n_cur, view(k_cache),
                             view(v_cache), len, resolve_scale(shape), out, st),
               "attend launch");
+  SCALEKV_HIP(mark(2), "event record");
   if (keep_out) *keep_out = keep;
   if (moved_out) *moved_out = moves ? 1 : 0;
   if (!moves) {  // everything is kept: the cache stays where it is
     if (idx_out)
       SCALEKV_HIP(launch_select(U, nullptr, 0, len, len, idx_out, nullptr, st), "select launch");
+    SCALEKV_HIP(mark(3), "event record");
+    SCALEKV_HIP(mark(4), "event record");
     return SCALEKV_OK;
   }
   // 3. scores of the window rows against the whole cache, pooled; window kept + top-budget
@@ -539,11 +548,13 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
       SCALEKV_HIP(fused, "fused select launch");
     }
   }
+  SCALEKV_HIP(mark(3), "event record");
   // 4. the kept rows become the next cache
   SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, d, view(k_cache),
                              view(v_cache), idx_ws, keep, nullptr, nullptr, 0, view(k_next),
                              view(v_next), st),
               "compact launch");
+  SCALEKV_HIP(mark(4), "event record");
   return SCALEKV_OK;
 }
 
