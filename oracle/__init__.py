@@ -1,4 +1,5 @@
-"""Python face of the fp64 CPU oracle (oracle/scalekv_oracle.c, oracle/selection_literal.c).
+"""Python face of the fp64 CPU oracle (oracle/scalekv_oracle.c, oracle/selection_literal.c,
+oracle/allocation.c).
 
 TEST INFRASTRUCTURE.  Only tests/, __graft_entry__.smoke() and bench.py's
 cpu_baseline leg may import this package.  It never imports the HIP binding and
@@ -34,6 +35,10 @@ def lib() -> ctypes.CDLL:
         _lib.scalekv_oracle_window_centroids.restype = ctypes.c_int
         _lib.scalekv_oracle_select_forced.restype = ctypes.c_int
         _lib.scalekv_oracle_step_append_first_batch.restype = ctypes.c_int
+        _lib.scalekv_oracle_asi.restype = ctypes.c_double
+        _lib.scalekv_oracle_drafters.restype = ctypes.c_int
+        _lib.scalekv_oracle_budgets.restype = ctypes.c_int
+        _lib.scalekv_oracle_positional.restype = ctypes.c_int
     return _lib
 
 
@@ -207,3 +212,72 @@ def step_append_first(q, k_cur, v_cur, win_idx: Sequence[int], k_cache, v_cache,
         _dp(v_next), _ip(idx), _dp(sc), _dp(out))
     return dict(out=out, scores=sc, idx=idx[:, :keep].copy(), k_next=k_next[:, :keep].copy(),
                 v_next=v_next[:, :keep].copy(), keep=int(keep))
+
+
+# ---- the offline policy: ASI, drafter set, budgets, comparison policies (oracle/allocation.c)
+
+def asi_terms(q, k, hist_len: int, top_k: int, scale: Optional[float] = None):
+    """Eq. 2, both factors per sampled query.  q [U, n_s, d]; k [U, hist_len + cur_len, d]
+    (history rows first).  Returns (cur_ratio [U, n_s], hist_topk [U, n_s])."""
+    q, k = _f64(q), _f64(k)
+    U, n_s, d = q.shape
+    cur_len = k.shape[1] - int(hist_len)
+    scale = default_scale(d) if scale is None else float(scale)
+    cur = np.zeros((U, n_s)); top = np.zeros((U, n_s))
+    for u in range(U):
+        lib().scalekv_oracle_asi_terms(_dp(q[u]), n_s, _dp(k[u]), int(hist_len), cur_len, d,
+                                       ctypes.c_double(scale), int(top_k), _dp(cur[u]), _dp(top[u]))
+    return cur, top
+
+
+def asi(cur_ratio, hist_topk) -> float:
+    """Eq. 2: product of the two means over every sampled query handed in."""
+    a, b = _f64(cur_ratio).ravel(), _f64(hist_topk).ravel()
+    return float(lib().scalekv_oracle_asi(_dp(a), _dp(b), a.size))
+
+
+def zscores(asi_lk, eps: float = 1e-8) -> np.ndarray:
+    """Eq. 3: per-scale Z-score of ASI [L, K]."""
+    a = _f64(asi_lk)
+    L, K = a.shape
+    z = np.zeros((L, K))
+    lib().scalekv_oracle_zscores(_dp(a), L, K, ctypes.c_double(eps), _dp(z))
+    return z
+
+
+def drafters(z, n_d: int) -> np.ndarray:
+    """Eq. 3: [L, K] int32 mask of the n_d pairs with the lowest Z."""
+    z = _f64(z)
+    L, K = z.shape
+    mask = np.zeros((L, K), dtype=np.int32)
+    lib().scalekv_oracle_drafters(_dp(z), L, K, int(n_d), _ip(mask))
+    return mask
+
+
+def budgets(L: int, n_d: Sequence[int], b_uniform: int, b_r0: int, delta: int, b_min: int = 0):
+    """Eq. 4 -> (b_r [K], b_d, slack) or None when it has no solution."""
+    n_d = np.ascontiguousarray(np.asarray(list(n_d), dtype=np.int32))
+    K = len(n_d)
+    b_r = np.zeros(K, dtype=np.int32)
+    b_d = ctypes.c_int32(0); slack = ctypes.c_longlong(0)
+    rc = lib().scalekv_oracle_budgets(int(L), K, _ip(n_d), ctypes.c_longlong(b_uniform),
+                                      ctypes.c_longlong(b_r0), ctypes.c_longlong(delta),
+                                      ctypes.c_longlong(b_min), _ip(b_r), ctypes.byref(b_d),
+                                      ctypes.byref(slack))
+    if rc != 0:
+        return None
+    return b_r, int(b_d.value), int(slack.value)
+
+
+def positional(length: int, n_sink: int, n_recent: int) -> np.ndarray:
+    """Sliding-window / sinks-and-recent positions of Sec. 4.1, ascending."""
+    idx = np.zeros(max(1, length), dtype=np.int32)
+    n = lib().scalekv_oracle_positional(int(length), int(n_sink), int(n_recent), _ip(idx))
+    return idx[:n].copy()
+
+
+def pyramid(L: int, b_uniform: int, b_last: int) -> np.ndarray:
+    """Pyramid-shaped per-layer budgets of Sec. 4.1 with mean b_uniform."""
+    b = np.zeros(L, dtype=np.int32)
+    lib().scalekv_oracle_pyramid(int(L), ctypes.c_longlong(b_uniform), ctypes.c_longlong(b_last), _ip(b))
+    return b

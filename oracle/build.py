@@ -8,7 +8,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, "scalekv_oracle.c"), os.path.join(HERE, "selection_literal.c")]
+SRCS = [os.path.join(HERE, n) for n in ("scalekv_oracle.c", "selection_literal.c", "allocation.c")]
 LIB = os.path.join(HERE, "libscalekv_oracle.so")
 
 
