@@ -52,6 +52,7 @@ extern "C" {
 
 #define SCALEKV_MAX_WINDOW 16
 #define SCALEKV_MAX_POOL 31
+#define SCALEKV_MAX_ASI_SAMPLES 1024
 
 typedef enum {
   SCALEKV_OK = 0,
@@ -201,6 +202,65 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
                                          int32_t* keep_out, int32_t* moved_out, void* out,
                                          int32_t* idx_out, void* ws, size_t ws_bytes,
                                          void* stream);
+
+/* ---- The offline policy that produces the per-(layer, scale) budget. ---- */
+
+/* Attention Selectivity Index, Eq. 2, for one layer at one scale.  q_samp [S,H,n_samp,d]:
+ * queries sampled from the current map (1 <= n_samp <= SCALEKV_MAX_ASI_SAMPLES).  k: cache
+ * whose rows [0, hist_len) are the history P_{k-1} and rows [hist_len, hist_len + cur_len)
+ * the current map C_k; each query's softmax runs over all of them (hist_len + cur_len >= 1).
+ *   terms [S,H,n_samp,2] fp32 device: per query, {attention mass on the current map,
+ *     sum of its top_k largest weights on history rows (all of them if hist_len < top_k)}.
+ *   asi_out (device, 3 floats, may be NULL): mean of the first term over all S*H*n_samp
+ *     queries, mean of the second, and their product, the ASI of Eq. 2.  Several calls
+ *     (more prompts) are combined by the caller from `terms`.
+ * Workspace: scalekv_workspace_bytes(shape, hist_len + cur_len, n_samp).  All sums run in a
+ * fixed order: results are reproducible bit for bit. */
+scalekv_status scalekv_asi(const scalekv_shape* shape, const void* q_samp, int32_t n_samp,
+                           const scalekv_kv* k, int32_t hist_len, int32_t cur_len, int32_t top_k,
+                           float* terms, float* asi_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 3.  Host only, no GPU work.  asi (host, [n_layer][n_scale] row-major, finite).
+ * Z = (ASI - mu_k) / (sigma_k + eps) with the mean and the population standard deviation
+ * over the layers of scale k (0 where sigma_k + eps == 0); the n_drafter pairs with the
+ * lowest Z over all layers and scales are the drafters, equal Z resolved towards the lower
+ * scale, then the lower layer.  is_drafter (host, [n_layer][n_scale]) receives 1 / 0; z_out
+ * (host, same shape, may be NULL) the Z-scores.  n_drafter beyond n_layer*n_scale takes all. */
+scalekv_status scalekv_drafter_set(const double* asi, int32_t n_layer, int32_t n_scale,
+                                   int32_t n_drafter, double eps, double* z_out,
+                                   int32_t* is_drafter);
+
+/* Eq. 4.  Host only.  n_drafter (host, [n_scale]): drafter layers at each scale, the other
+ * n_layer - n_drafter[k] layers are refiners.  Refiner budget at scale k (k = 1..n_scale as in
+ * the equation's sum): b_r[k-1] = max(b_min, b_r0 - delta * k).  The drafter budget is one
+ * value for all scales, *b_d = floor((b_uniform * n_layer * n_scale - sum_k N_r^k B_r(k)) /
+ * sum_k N_d^k); *slack (may be NULL) = the tokens by which the left side of Eq. 4 then falls
+ * short of the right, 0 <= slack < sum_k N_d^k.  All budgets are tokens per head.
+ * Errors (INVALID_ARG): no drafter at any scale; refiner budgets alone above the total;
+ * negative inputs or inputs above 2^31-1. */
+scalekv_status scalekv_allocate_budgets(int32_t n_layer, int32_t n_scale, const int32_t* n_drafter,
+                                        int64_t b_uniform, int64_t b_r0, int64_t delta,
+                                        int64_t b_min, int32_t* b_r, int32_t* b_d, int64_t* slack);
+
+/* ---- Comparison policies of Sec. 4.1 ("Compression Baselines"), as index / budget
+ * generators for the same compact and attend calls; each is built from the one line the
+ * paper gives it. ---- */
+
+/* Position-only retention: the first min(n_sink, cache_len) rows and the last
+ * min(n_recent, rest) rows of every unit (n_sink = 0: sliding window of the most recent
+ * tokens; n_sink > 0: attention sinks plus recent tokens).  idx [S,H,keep] int32 device,
+ * ascending; *keep_out (host, may be NULL) = keep, valid on return. */
+scalekv_status scalekv_select_positional(const scalekv_shape* shape, int32_t cache_len,
+                                         int32_t n_sink, int32_t n_recent, int32_t* idx,
+                                         int32_t* keep_out, void* stream);
+
+/* Pyramid-shaped allocation across layers.  Host only.  b (host, [n_layer]) falls linearly
+ * from 2*b_uniform - b_last at the first layer to b_last at the last (0 <= b_last <=
+ * b_uniform): b[l] = b_first - floor((b_first - b_last) * l / (n_layer - 1)) in the lower
+ * half, b[n_layer-1-l] = 2*b_uniform - b[l] in the upper, the middle layer of an odd count
+ * gets b_uniform; the sum is exactly n_layer * b_uniform. */
+scalekv_status scalekv_pyramid_budgets(int32_t n_layer, int64_t b_uniform, int64_t b_last,
+                                       int32_t* b);
 
 /* Benchmark aid, not part of the method.  events: host array of 5 hipEvent_t
  * (created by the caller with timing enabled), or NULL to switch off.  While

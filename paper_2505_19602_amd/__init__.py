@@ -24,7 +24,13 @@ from .binding import (  # noqa: F401
     window_centroids,
     select_window,
     step_append_first,
+    asi,
+    drafter_set,
+    allocate_budgets,
+    pyramid_budgets,
+    select_positional,
     MAX_WINDOW,
+    MAX_ASI_SAMPLES,
     MAX_POOL,
     EXPORTED_SYMBOLS,
 )

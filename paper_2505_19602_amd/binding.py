@@ -18,12 +18,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 MAX_WINDOW = 16
 
 MAX_POOL = 31
+MAX_ASI_SAMPLES = 1024
 
 # status-returning entry points first, then the two that return strings
 _STATUS_SYMBOLS = (
     "scalekv_workspace_bytes", "scalekv_score", "scalekv_select", "scalekv_compact",
     "scalekv_attend", "scalekv_step", "scalekv_step_stage_events",
     "scalekv_window_centroids", "scalekv_select_window", "scalekv_step_append_first",
+    "scalekv_asi", "scalekv_drafter_set", "scalekv_allocate_budgets", "scalekv_select_positional",
+    "scalekv_pyramid_budgets",
 )
 EXPORTED_SYMBOLS = _STATUS_SYMBOLS + ("scalekv_last_error", "scalekv_version")
 
@@ -381,3 +384,67 @@ def step_append_first(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur:
         ctypes.byref(c) if c is not None else None, ctypes.byref(d) if d is not None else None,
         ctypes.byref(keep_out), ctypes.byref(moved), _ptr(out), _ptr(idx_out), wp, wb, _stream()))
     return int(keep_out.value), bool(moved.value)
+
+
+# ---- the offline policy (Eq. 2-4) and the comparison policies of Sec. 4.1
+
+def asi(shape: Shape, q_samp: torch.Tensor, k: torch.Tensor, hist_len: int, cur_len: int, top_k: int,
+        terms: torch.Tensor, asi_out: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    """scalekv_asi: q_samp [S,H,n_samp,d], k cache (history rows then the current map) ->
+    terms [S,H,n_samp,2] fp32 and, if given, asi_out [3] fp32 (two means and their product)."""
+    n_samp = q_samp.shape[2]
+    _dense(q_samp, shape, n_samp, "q_samp")
+    if terms.dtype != torch.float32 or not terms.is_cuda or not terms.is_contiguous() \
+            or tuple(terms.shape) != (shape.n_seq, shape.n_head, n_samp, 2):
+        raise ScaleKVError(1, "terms must be a contiguous fp32 device tensor [S,H,n_samp,2]")
+    if asi_out is not None and (asi_out.dtype != torch.float32 or not asi_out.is_cuda
+                                or not asi_out.is_contiguous() or asi_out.numel() != 3):
+        raise ScaleKVError(1, "asi_out must be a contiguous fp32 device tensor of 3 elements")
+    cs, ck = shape.c(), _kv(k, shape, "k")
+    wp, wb = _ws(ws)
+    _check(lib().scalekv_asi(ctypes.byref(cs), _ptr(q_samp), int(n_samp), ctypes.byref(ck), int(hist_len),
+                             int(cur_len), int(top_k), _ptr(terms), _ptr(asi_out), wp, wb, _stream()))
+
+
+def drafter_set(asi_lk, n_drafter: int, eps: float = 1e-8):
+    """scalekv_drafter_set: asi_lk is a [L][K] nested sequence of floats (host).
+    Returns (is_drafter [L][K] of 0/1, z [L][K])."""
+    L, K = len(asi_lk), len(asi_lk[0])
+    flat = (ctypes.c_double * (L * K))(*[float(x) for row in asi_lk for x in row])
+    z = (ctypes.c_double * (L * K))()
+    mask = (ctypes.c_int32 * (L * K))()
+    _check(lib().scalekv_drafter_set(flat, int(L), int(K), int(n_drafter), ctypes.c_double(eps), z, mask))
+    return ([[int(mask[l * K + k]) for k in range(K)] for l in range(L)],
+            [[float(z[l * K + k]) for k in range(K)] for l in range(L)])
+
+
+def allocate_budgets(n_layer: int, n_drafter: Sequence[int], b_uniform: int, b_r0: int, delta: int,
+                     b_min: int = 0):
+    """scalekv_allocate_budgets -> (b_r [K], b_d, slack)."""
+    K = len(n_drafter)
+    nd = (ctypes.c_int32 * max(1, K))(*[int(x) for x in n_drafter])
+    b_r = (ctypes.c_int32 * max(1, K))()
+    b_d, slack = ctypes.c_int32(-1), ctypes.c_int64(-1)
+    _check(lib().scalekv_allocate_budgets(int(n_layer), int(K), nd, ctypes.c_int64(b_uniform),
+                                          ctypes.c_int64(b_r0), ctypes.c_int64(delta), ctypes.c_int64(b_min),
+                                          b_r, ctypes.byref(b_d), ctypes.byref(slack)))
+    return [int(b_r[k]) for k in range(K)], int(b_d.value), int(slack.value)
+
+
+def pyramid_budgets(n_layer: int, b_uniform: int, b_last: int) -> list:
+    """scalekv_pyramid_budgets -> per-layer budgets [L]."""
+    b = (ctypes.c_int32 * max(1, n_layer))()
+    _check(lib().scalekv_pyramid_budgets(int(n_layer), ctypes.c_int64(b_uniform), ctypes.c_int64(b_last), b))
+    return [int(b[l]) for l in range(n_layer)]
+
+
+def select_positional(shape: Shape, cache_len: int, n_sink: int, n_recent: int, idx: torch.Tensor) -> int:
+    """scalekv_select_positional: first n_sink and last n_recent positions -> idx [S,H,keep]; returns keep."""
+    sink = max(0, min(int(n_sink), int(cache_len)))
+    keep = sink + max(0, min(int(n_recent), int(cache_len) - sink))
+    _idx_tensor(idx, shape, keep, "idx")
+    cs = shape.c()
+    out = ctypes.c_int32(-1)
+    _check(lib().scalekv_select_positional(ctypes.byref(cs), int(cache_len), int(n_sink), int(n_recent),
+                                           _ptr(idx), ctypes.byref(out), _stream()))
+    return int(out.value)

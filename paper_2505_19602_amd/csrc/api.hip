@@ -4,6 +4,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <algorithm>
+#include <cmath>
+#include <vector>
 
 #include "../../include/scalekv.h"
 #include "common.h"
@@ -555,6 +558,155 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
                              view(v_next), st),
               "compact launch");
   SCALEKV_HIP(mark(4), "event record");
+  return SCALEKV_OK;
+}
+
+// ---- offline policy: ASI (Eq. 2), drafter set (Eq. 3), budgets (Eq. 4), comparison policies
+
+scalekv_status scalekv_asi(const scalekv_shape* shape, const void* q_samp, int32_t n_samp,
+                           const scalekv_kv* k, int32_t hist_len, int32_t cur_len, int32_t top_k,
+                           float* terms, float* asi_out, void* ws, size_t ws_bytes, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  if (n_samp < 1 || n_samp > SCALEKV_MAX_ASI_SAMPLES)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_samp %d is outside 1..%d", n_samp,
+                SCALEKV_MAX_ASI_SAMPLES);
+  if (top_k < 0) return fail(SCALEKV_ERR_INVALID_ARG, "top_k is negative (%d)", top_k);
+  SCALEKV_TRY(check_rows(shape, hist_len, "hist_len"));
+  SCALEKV_TRY(check_rows(shape, cur_len, "cur_len"));
+  const long long len_ll = (long long)hist_len + cur_len;
+  SCALEKV_TRY(check_rows(shape, len_ll, "hist_len + cur_len"));
+  if (len_ll < 1) return fail(SCALEKV_ERR_INVALID_ARG, "hist_len + cur_len must be >= 1");
+  const int len = (int)len_ll;
+  SCALEKV_TRY(check_dense(q_samp, true, "q_samp"));
+  SCALEKV_TRY(check_kv(shape, k, len, "k"));
+  if (!terms) return fail(SCALEKV_ERR_INVALID_ARG, "terms is NULL");
+  SCALEKV_TRY(check_ws(shape, len, ws, ws_bytes));
+  const WsLayout w = ws_layout(shape, len);
+  const ScoreWorkspace sw = score_ws(w, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int U = shape->n_seq * shape->n_head;
+  for (int row0 = 0; row0 < n_samp; row0 += kMaxWindow) {
+    const int n_rows = std::min(kMaxWindow, n_samp - row0);
+    WindowRows rows;
+    for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = row0 + (j < n_rows ? j : 0);
+    SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
+                                    q_samp, (long long)n_samp * shape->head_dim, rows, n_rows,
+                                    view(k), len, resolve_scale(shape), sw, st),
+                "asi logits launch");
+    SCALEKV_HIP(launch_asi_terms(U, sw, n_rows, hist_len, len, top_k, terms, n_samp, row0, st),
+                "asi terms launch");
+  }
+  if (asi_out)
+    SCALEKV_HIP(launch_asi_mean(terms, (long long)U * n_samp, asi_out, st), "asi mean launch");
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_drafter_set(const double* asi, int32_t n_layer, int32_t n_scale,
+                                   int32_t n_drafter, double eps, double* z_out,
+                                   int32_t* is_drafter) {
+  if (n_layer < 1 || n_scale < 1)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_layer and n_scale must be positive (got %d, %d)",
+                n_layer, n_scale);
+  if ((long long)n_layer * n_scale > 0x7fffffffLL)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "n_layer * n_scale is too large");
+  if (n_drafter < 0) return fail(SCALEKV_ERR_INVALID_ARG, "n_drafter is negative (%d)", n_drafter);
+  if (!(eps >= 0.0)) return fail(SCALEKV_ERR_INVALID_ARG, "eps must be >= 0");
+  if (!asi || !is_drafter) return fail(SCALEKV_ERR_INVALID_ARG, "asi or is_drafter is NULL");
+  const int L = n_layer, K = n_scale, total = L * K;
+  for (int i = 0; i < total; ++i)
+    if (!std::isfinite(asi[i])) return fail(SCALEKV_ERR_INVALID_ARG, "asi[%d] is not finite", i);
+  std::vector<double> z((size_t)total);
+  for (int k = 0; k < K; ++k) {
+    double sum = 0.0;
+    for (int l = 0; l < L; ++l) sum += asi[(size_t)l * K + k];
+    const double mu = sum / L;
+    double ss = 0.0;
+    for (int l = 0; l < L; ++l) ss += (asi[(size_t)l * K + k] - mu) * (asi[(size_t)l * K + k] - mu);
+    const double denom = std::sqrt(ss / L) + eps;  // population deviation of the scale
+    for (int l = 0; l < L; ++l)
+      z[(size_t)l * K + k] = denom > 0.0 ? (asi[(size_t)l * K + k] - mu) / denom : 0.0;
+  }
+  // rank every (layer, scale) pair by (Z, scale, layer) and take the first n_drafter
+  std::vector<int> order((size_t)total);
+  for (int i = 0; i < total; ++i) order[i] = i;
+  std::sort(order.begin(), order.end(), [&](int a, int b) {
+    if (z[a] != z[b]) return z[a] < z[b];
+    const int ka = a % K, kb = b % K;
+    if (ka != kb) return ka < kb;
+    return a / K < b / K;
+  });
+  const int take = std::min(n_drafter, total);
+  for (int i = 0; i < total; ++i) is_drafter[i] = 0;
+  for (int i = 0; i < take; ++i) is_drafter[order[i]] = 1;
+  if (z_out) std::memcpy(z_out, z.data(), (size_t)total * sizeof(double));
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_allocate_budgets(int32_t n_layer, int32_t n_scale, const int32_t* n_drafter,
+                                        int64_t b_uniform, int64_t b_r0, int64_t delta,
+                                        int64_t b_min, int32_t* b_r, int32_t* b_d, int64_t* slack) {
+  if (n_layer < 1 || n_scale < 1)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_layer and n_scale must be positive (got %d, %d)",
+                n_layer, n_scale);
+  if (!n_drafter || !b_r || !b_d) return fail(SCALEKV_ERR_INVALID_ARG, "n_drafter, b_r or b_d is NULL");
+  constexpr int64_t kMax = 0x7fffffffLL;
+  if (b_uniform < 0 || b_r0 < 0 || delta < 0 || b_min < 0 || b_uniform > kMax || b_r0 > kMax ||
+      delta > kMax || b_min > kMax)
+    return fail(SCALEKV_ERR_INVALID_ARG, "b_uniform, b_r0, delta and b_min must be in 0..2^31-1");
+  int64_t n_d_total = 0, refiner_tokens = 0;
+  for (int k = 0; k < n_scale; ++k) {
+    if (n_drafter[k] < 0 || n_drafter[k] > n_layer)
+      return fail(SCALEKV_ERR_INVALID_ARG, "n_drafter[%d] = %d is outside 0..n_layer", k,
+                  n_drafter[k]);
+    n_d_total += n_drafter[k];
+    refiner_tokens += (int64_t)(n_layer - n_drafter[k]) * std::max(b_min, b_r0 - delta * (k + 1));
+  }
+  const int64_t target = b_uniform * n_layer * n_scale;
+  if (n_d_total == 0)
+    return fail(SCALEKV_ERR_INVALID_ARG, "no drafter layer at any scale: nothing can take the pool");
+  if (refiner_tokens > target)
+    return fail(SCALEKV_ERR_INVALID_ARG,
+                "the refiner budgets alone (%lld tokens) exceed the uniform total (%lld)",
+                (long long)refiner_tokens, (long long)target);
+  const int64_t each = (target - refiner_tokens) / n_d_total;
+  if (each > kMax) return fail(SCALEKV_ERR_UNSUPPORTED, "drafter budget does not fit int32");
+  for (int k = 0; k < n_scale; ++k) b_r[k] = (int32_t)std::max(b_min, b_r0 - delta * (k + 1));
+  *b_d = (int32_t)each;
+  if (slack) *slack = target - refiner_tokens - each * n_d_total;
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_pyramid_budgets(int32_t n_layer, int64_t b_uniform, int64_t b_last,
+                                       int32_t* b) {
+  if (n_layer < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_layer must be positive (got %d)", n_layer);
+  if (!b) return fail(SCALEKV_ERR_INVALID_ARG, "b is NULL");
+  if (b_uniform < 0 || b_uniform > 0x3fffffffLL || b_last < 0 || b_last > b_uniform)
+    return fail(SCALEKV_ERR_INVALID_ARG, "need 0 <= b_last <= b_uniform < 2^30");
+  const int64_t span = 2 * (b_uniform - b_last);  // first layer's budget minus the last layer's
+  for (int l = 0; 2 * l < n_layer - 1; ++l) {
+    const int64_t drop = span * l / (n_layer - 1);
+    b[l] = (int32_t)(b_last + span - drop);
+    b[n_layer - 1 - l] = (int32_t)(b_last + drop);
+  }
+  if (n_layer % 2) b[n_layer / 2] = (int32_t)b_uniform;
+  return SCALEKV_OK;
+}
+
+scalekv_status scalekv_select_positional(const scalekv_shape* shape, int32_t cache_len,
+                                         int32_t n_sink, int32_t n_recent, int32_t* idx,
+                                         int32_t* keep_out, void* stream) {
+  SCALEKV_TRY(check_shape(shape));
+  SCALEKV_TRY(check_rows(shape, cache_len, "cache_len"));
+  if (n_sink < 0 || n_recent < 0)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_sink and n_recent must be >= 0 (got %d, %d)", n_sink,
+                n_recent);
+  const int sink = std::min(n_sink, cache_len);
+  const int keep = sink + std::min(n_recent, cache_len - sink);
+  if (keep > 0 && !idx) return fail(SCALEKV_ERR_INVALID_ARG, "idx is NULL");
+  if (keep_out) *keep_out = keep;
+  SCALEKV_HIP(launch_positional(shape->n_seq * shape->n_head, cache_len, sink, keep, idx,
+                                static_cast<hipStream_t>(stream)),
+              "positional launch");
   return SCALEKV_OK;
 }
 

@@ -55,6 +55,16 @@ hipError_t launch_select(int n_unit, const float* scores, long long score_unit_s
 hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
                                      int keep, int32_t* idx, const SelectExtras* extras,
                                      hipStream_t stream);
+// first n_sink and last keep - n_sink positions of every unit (n_sink <= keep <= cache_len)
+hipError_t launch_positional(int n_unit, int cache_len, int n_sink, int keep, int32_t* idx,
+                             hipStream_t stream);
+// Eq. 2 for the n_rows (<= kMaxWindow) query rows whose logits sit in `ws`: per row the
+// attention mass on keys [hist_len, len) and the sum of its top_k largest weights on keys
+// [0, hist_len), written to terms[((unit * n_samp) + row0 + row) * 2 + {0, 1}]
+hipError_t launch_asi_terms(int n_unit, ScoreWorkspace ws, int n_rows, int hist_len, int len,
+                            int top_k, float* terms, int n_samp, int row0, hipStream_t stream);
+// out[0], out[1] = means of the two columns of terms [n][2]; out[2] = their product
+hipError_t launch_asi_mean(const float* terms, long long n, float* out, hipStream_t stream);
 hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src, KvView v_src,
                           const int32_t* idx, int keep, const void* k_cur, const void* v_cur,
                           int n_cur, KvView k_dst, KvView v_dst, hipStream_t stream);

@@ -12,6 +12,7 @@
 // that are preserved whatever their score (the observation window): those get the
 // largest key, and `keep` counts them.
 #include "common.h"
+#include "radix_select.h"
 
 namespace scalekv {
 namespace {
@@ -19,11 +20,6 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kLdsKeys = 12288;  // units up to this many scores keep their keys in LDS
-
-__device__ __forceinline__ uint32_t order_key(float f) {
-  const uint32_t b = __float_as_uint(f + 0.0f);  // -0 and +0 rank equal
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
 
 // FUSED: the scores are not read but formed here from the logits workspace (the score
 // finalisation), so the fused step neither writes nor re-reads them.
@@ -51,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
   __shared__ float row_shift[kMaxWindow];
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t sel_bin, sel_remaining;
+  __shared__ uint32_t sel[2];
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
 
   const int unit = blockIdx.x;
@@ -101,46 +97,8 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   }
 
   // ---- radix select: T = key of the keep-th largest ----
-  uint32_t prefix = 0, mask = 0, remaining = keep;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int i = tid; i < cache_len; i += kThreads) {
-      const uint32_t kk = key_at(i);
-      if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    if (tid < 64) {
-      // lane L owns bins 4L..4L+3; `above` = count in all bins higher than the lane's.
-      const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2],
-                     h3 = hist[4 * tid + 3];
-      const uint32_t mine = h0 + h1 + h2 + h3;
-      uint32_t incl = mine;  // inclusive suffix sum over lanes >= tid
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t other = __shfl_down(incl, off);
-        if (tid + off < 64) incl += other;
-      }
-      uint32_t above = incl - mine;
-      // walk the lane's bins from the top
-      const uint32_t hh[4] = {h3, h2, h1, h0};
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        if (above < remaining && remaining <= above + hh[b]) {
-          sel_bin = 4 * tid + (3 - b);
-          sel_remaining = remaining - above;
-        }
-        above += hh[b];
-      }
-    }
-    __syncthreads();
-    prefix |= sel_bin << shift;
-    mask |= 255u << shift;
-    remaining = sel_remaining;
-    __syncthreads();
-  }
-  const uint32_t T = prefix;
-  const uint32_t need_eq = remaining;  // how many keys equal to T are taken (>= 1)
+  uint32_t T, need_eq;  // need_eq: how many keys equal to T are taken (>= 1)
+  radix_kth_largest<kThreads>(key_at, cache_len, (uint32_t)keep, hist, sel, T, need_eq);
 
   // ---- stable emission ----
   const int per = (cache_len + kThreads - 1) / kThreads;
@@ -183,7 +141,27 @@ __global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total
   if (e < total) idx[e] = (int32_t)(e % keep);
 }
 
+// Position-only retention (the sliding-window and sinks-plus-recent policies the paper
+// compares against in Sec. 4.1): every unit keeps the first n_sink and the last
+// keep - n_sink positions of its cache_len rows.
+__global__ void positional_kernel(int32_t* __restrict__ idx, int keep, int n_sink, int cache_len,
+                                  long long total) {
+  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int t = (int)(e % keep);
+  idx[e] = t < n_sink ? t : cache_len - keep + t;
+}
+
 }  // namespace
+
+hipError_t launch_positional(int n_unit, int cache_len, int n_sink, int keep, int32_t* idx,
+                             hipStream_t stream) {
+  if (n_unit <= 0 || keep <= 0) return hipSuccess;
+  const long long total = (long long)n_unit * keep;
+  hipLaunchKernelGGL(positional_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     stream, idx, keep, n_sink, cache_len, total);
+  return hipGetLastError();
+}
 
 hipError_t launch_select(int n_unit, const float* scores, long long score_unit_stride,
                          int cache_len, int keep, int32_t* idx, const SelectExtras* extras,

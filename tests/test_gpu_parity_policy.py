@@ -1,0 +1,125 @@
+"""GPU parity for the offline policy and the comparison policies: scalekv_asi (Eq. 2)
+and scalekv_select_positional (Sec. 4.1) through the C ABI against the oracle, and the
+positional indices driving the same compact / attend kernels as the method's own."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_19602_amd as skv
+import workloads as W
+from parity_util import check_output, units
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+# ASI terms are sums of fp32 softmax weights formed from fp32-accumulated logits: the
+# logits carry <= 2e-4 absolute error (the bound used for the log-scores), so every weight
+# and each of the two sums carries <= ~5e-4 relative error.
+ASI_RTOL, ASI_ATOL = 1e-3, 1e-6
+
+
+def _rand(key, shape, dtype, scale=1.0):
+    return (W.normal_tensor(W.stream_key(4321, key), shape) * scale).to(dtype)
+
+
+def _note(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("dtype,d,hist,cur,n_samp,top_k,qscale", [
+    (torch.bfloat16, 128, 700, 300, 16, 32, 1.0),
+    (torch.bfloat16, 128, 1000, 37, 5, 1, 3.0),       # ragged rows, peaked rows
+    (torch.bfloat16, 128, 6489, 4096, 40, 64, 2.0),   # last scale of the 1024^2 schedule, 3 row groups
+    (torch.bfloat16, 64, 300, 64, 20, 500, 1.0),      # top_k beyond the history: whole history
+    (torch.float32, 64, 333, 100, 9, 10, 2.0),
+    (torch.float32, 128, 0, 50, 3, 4, 1.0),           # no history yet
+    (torch.bfloat16, 128, 80, 0, 16, 8, 1.0),         # no current rows
+    (torch.bfloat16, 128, 13000, 500, 4, 100, 2.0),   # history beyond the LDS-resident size
+])
+def test_asi_matches_oracle(dtype, d, hist, cur, n_samp, top_k, qscale):
+    S, H = 2, 2
+    _note(f"asi dtype={dtype} d={d} hist={hist} cur={cur} n_samp={n_samp} top_k={top_k}")
+    shape = skv.Shape(S, H, d, dtype)
+    n = hist + cur
+    q = _rand(1, (S, H, n_samp, d), dtype, qscale)
+    k = _rand(2, (S, H, n + 7, d), dtype)                 # capacity beyond the rows in use
+    terms = torch.full((S, H, n_samp, 2), -1.0, dtype=torch.float32, device=DEV)
+    out3 = torch.full((3,), -1.0, dtype=torch.float32, device=DEV)
+    ws = torch.zeros(skv.workspace_bytes(shape, n, n_samp), dtype=torch.uint8, device=DEV)
+    skv.asi(shape, q.to(DEV), k.to(DEV), hist, cur, top_k, terms, out3, ws)
+    torch.cuda.synchronize()
+    c_ref, t_ref = oracle.asi_terms(units(q), units(k)[:, :n], hist, top_k)
+    got = terms.cpu().numpy().reshape(S * H, n_samp, 2).astype(np.float64)
+    assert np.allclose(got[..., 0], c_ref, rtol=ASI_RTOL, atol=ASI_ATOL), np.abs(got[..., 0] - c_ref).max()
+    assert np.allclose(got[..., 1], t_ref, rtol=ASI_RTOL, atol=ASI_ATOL), np.abs(got[..., 1] - t_ref).max()
+    o = out3.cpu().numpy().astype(np.float64)
+    assert np.isclose(o[0], c_ref.mean(), rtol=ASI_RTOL, atol=ASI_ATOL)
+    assert np.isclose(o[1], t_ref.mean(), rtol=ASI_RTOL, atol=ASI_ATOL)
+    assert np.isclose(o[2], oracle.asi(c_ref, t_ref), rtol=2 * ASI_RTOL, atol=ASI_ATOL)
+    # fixed summation order: a second run gives the same bits
+    terms2 = torch.zeros_like(terms)
+    skv.asi(shape, q.to(DEV), k.to(DEV), hist, cur, top_k, terms2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(terms, terms2)
+
+
+def test_asi_separates_a_spread_layer_from_a_focused_one():
+    # Sec. 3.3: low ASI = attention spread over the prefix (drafter), high ASI = mass on the
+    # current map or on a few history tokens (refiner).  Same keys, queries at two temperatures.
+    S, H, d, hist, cur = 1, 4, 128, 900, 256
+    dtype = torch.bfloat16
+    shape = skv.Shape(S, H, d, dtype)
+    k = _rand(7, (S, H, hist + cur, d), dtype)
+    ws = torch.zeros(skv.workspace_bytes(shape, hist + cur, 16), dtype=torch.uint8, device=DEV)
+    asis = []
+    for qscale in (0.05, 6.0):
+        # focused queries: aligned with current-map keys 0..15
+        q = (k[:, :, hist:hist + 16].float() * qscale).to(dtype)
+        terms = torch.zeros(S, H, 16, 2, dtype=torch.float32, device=DEV)
+        out3 = torch.zeros(3, dtype=torch.float32, device=DEV)
+        skv.asi(shape, q.to(DEV), k.to(DEV), hist, cur, 16, terms, out3, ws)
+        torch.cuda.synchronize()
+        c_ref, t_ref = oracle.asi_terms(units(q), units(k), hist, 16)
+        assert np.isclose(out3[2].item(), oracle.asi(c_ref, t_ref), rtol=2 * ASI_RTOL, atol=ASI_ATOL)
+        asis.append(out3[2].item())
+    mask, _ = skv.drafter_set([[asis[0]], [asis[1]]], 1)
+    assert mask == [[1], [0]]
+
+
+@pytest.mark.parametrize("L,n_sink,n_recent", [(1000, 0, 64), (1000, 4, 60), (50, 30, 40), (10, 0, 0), (0, 2, 2),
+                                               (6489, 64, 585)])
+def test_select_positional_matches_oracle(L, n_sink, n_recent):
+    S, H = 2, 3
+    _note(f"positional L={L} sink={n_sink} recent={n_recent}")
+    shape = skv.Shape(S, H, 128, torch.bfloat16)
+    want = oracle.positional(L, n_sink, n_recent)
+    idx = torch.full((S, H, len(want)), -1, dtype=torch.int32, device=DEV)
+    keep = skv.select_positional(shape, L, n_sink, n_recent, idx)
+    torch.cuda.synchronize()
+    assert keep == len(want)
+    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(want, (S, H, len(want))))
+
+
+def test_positional_indices_drive_the_same_compact_and_attend():
+    # sinks + recent as the retention rule of one step: select_positional -> compact -> attend
+    S, H, d, L, n_cur, n_sink, n_recent = 1, 2, 128, 400, 150, 8, 56
+    dtype = torch.bfloat16
+    _note("positional policy end to end")
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = _rand(20, (S, H, n_cur, d), dtype), _rand(21, (S, H, n_cur, d), dtype), _rand(22, (S, H, n_cur, d), dtype)
+    ks, vs = _rand(23, (S, H, L, d), dtype), _rand(24, (S, H, L, d), dtype)
+    keep = n_sink + n_recent
+    idx = torch.zeros(S, H, keep, dtype=torch.int32, device=DEV)
+    assert skv.select_positional(shape, L, n_sink, n_recent, idx) == keep
+    kd = torch.zeros(S, H, keep + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+    new_len = skv.compact(shape, ks.to(DEV), vs.to(DEV), L, idx, keep, kc.to(DEV), vc.to(DEV), kd, vd)
+    out = torch.zeros(S, H, n_cur, d, dtype=dtype, device=DEV)
+    skv.attend(shape, q.to(DEV), kd, vd, new_len, out)
+    torch.cuda.synchronize()
+    oi = np.broadcast_to(oracle.positional(L, n_sink, n_recent), (S * H, keep))
+    k_ref = oracle.compact(units(ks).double(), oi, units(kc).double())
+    v_ref = oracle.compact(units(vs).double(), oi, units(vc).double())
+    assert np.array_equal(units(kd).double().numpy(), k_ref)
+    ref = oracle.attend(units(q), k_ref, v_ref)
+    check_output(out, ref, dtype, "positional policy attend")
