@@ -74,8 +74,9 @@ def test_asi_separates_a_spread_layer_from_a_focused_one():
     ws = torch.zeros(skv.workspace_bytes(shape, hist + cur, 16), dtype=torch.uint8, device=DEV)
     asis = []
     for qscale in (0.05, 6.0):
-        # focused queries: aligned with current-map keys 0..15
-        q = (k[:, :, hist:hist + 16].float() * qscale).to(dtype)
+        # query t points at current-map key t and history key t alike: at the low temperature the
+        # row is nearly uniform, at the high one its mass splits between those two keys
+        q = ((k[:, :, hist:hist + 16].float() + k[:, :, :16].float()) * qscale).to(dtype)
         terms = torch.zeros(S, H, 16, 2, dtype=torch.float32, device=DEV)
         out3 = torch.zeros(3, dtype=torch.float32, device=DEV)
         skv.asi(shape, q.to(DEV), k.to(DEV), hist, cur, 16, terms, out3, ws)
