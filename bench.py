@@ -13,6 +13,16 @@ recorded around its launches, on the launch stream, inside the timed region;
 per-stage times and bandwidths from one more, untimed pass with an event at every
 stage boundary; and the fp64 CPU oracle timed on a bounded sample of the same
 workload.
+
+--variant picks what each (layer, scale) call is; the default is the graded path:
+  scalekv   scalekv_step: score -> select -> compact -> attend, drafter/refiner budgets
+  literal   scalekv_step_append_first: Sec. 3.3 in its literal order (append, attend, then
+            score over history and map, pooled scores, window kept), 4x4 patch-centroid window
+  pyramid   scalekv_step with the per-layer pyramid budgets of scalekv_pyramid_budgets
+  sliding   scalekv_select_positional (most recent tokens) -> compact -> attend, uniform budget
+  sinks     the same with the first 16 positions kept as well
+The last three are the comparison policies of Sec. 4.1 at the same total budget: their cost,
+not their quality.
 """
 from __future__ import annotations
 
@@ -44,6 +54,18 @@ ATTEND_PIPE_TRAFFIC = {
     (2304, 1046): 932.8e6, (2304, 209): 744.5e6,
     (4096, 1622): 1286.6e6, (4096, 324): 1116.4e6,
 }
+
+
+VARIANTS = ("scalekv", "literal", "pyramid", "sliding", "sinks")
+# stages between consecutive events of one call, per variant
+STAGES = {
+    "scalekv": ("score", "select", "compact", "attend"),
+    "pyramid": ("score", "select", "compact", "attend"),
+    "literal": ("append", "attend", "score+select", "compact"),
+    "sliding": ("select", "compact", "attend"),
+    "sinks": ("select", "compact", "attend"),
+}
+N_SINK = 16
 
 
 def log(msg: str) -> None:
@@ -129,6 +151,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-pass", action="store_true",
                     help="skip the extra, untimed pass that records events at every stage boundary")
+    ap.add_argument("--variant", default="scalekv", choices=VARIANTS)
+    ap.add_argument("--pool-w", type=int, default=7, help="score pooling width of --variant literal")
     ap.add_argument("--shared-inputs", action="store_true",
                     help="reuse layer 0's Q/K/V in every layer (less memory, faster set-up)")
     args = ap.parse_args()
@@ -152,6 +176,14 @@ def main() -> int:
     shape = skv.Shape(S, H, d, dtype)
     cap = W.dst_capacity(cfg)
     table = W.budget_table(cfg)
+    # total retained fraction of the drafter/refiner table: the uniform budget of the comparison policies
+    uniform_frac = (cfg.n_drafter * cfg.drafter_frac + (Lyr - cfg.n_drafter) * cfg.refiner_frac) / Lyr
+    if args.variant == "literal":   # the cache buffer also holds the map before pruning
+        cap = max(cap, max(W.c_full(cfg, k) + cfg.n_tokens(k) for k in range(1, cfg.first_compressed_scale)),
+                  max(16 + max(r[k - 2] for r in table) + cfg.n_tokens(k) for k in range(2, K + 1)))
+    if args.variant == "pyramid":
+        cap = max(int(2 * uniform_frac * W.c_full(cfg, k) + 1) + cfg.n_tokens(k) for k in range(1, K + 1))
+        cap = max(cap, W.dst_capacity(cfg))
     log(f"{skv.version()}  workload {cfg.name}: S={S} H={H} d={d} layers={Lyr} scales={K} cap={cap}")
 
     # ---- resident state: prefix caches, ping-pong caches, per-(layer, scale) inputs
@@ -173,40 +205,125 @@ def main() -> int:
     out = torch.empty(S, H, max_q, d, dtype=dtype, device=dev)
     outs = {k: out.view(-1)[: U * cfg.n_tokens(k) * d].view(S, H, cfg.n_tokens(k), d) for k in range(1, K + 1)}
     windows = {k: W.window_indices(cfg, cfg.n_tokens(k)) for k in range(1, K + 1)}
+    centroids = {k: skv.window_centroids(cfg.sides[k - 1], cfg.sides[k - 1], 4, 4) for k in range(1, K + 1)}
+    idx_buf = torch.empty(U * cap, dtype=torch.int32, device=dev)
     log(f"set-up {time.perf_counter() - t_setup:.1f} s")
 
     events = HipEvents(skv.lib())
 
-    # Marshal the 416 calls once: the cache lengths follow from the budgets, so every
-    # argument of every call is known before anything runs.
+    # Marshal the calls once: the cache lengths follow from the budgets, so every argument of
+    # every call is known before anything runs.
+    variant = args.variant
+    stages = STAGES[variant]
+    att = stages.index("attend")            # the attend kernel runs between events att and att + 1
+    hip = skv.lib()
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    stream_ptr = torch.cuda.current_stream().cuda_stream
+
+    class LibCall:
+        """scalekv_step / scalekv_step_append_first; stage events through the library's hook"""
+        def __init__(self, prepared):
+            self.p = prepared
+
+        def run(self, ev):
+            if ev is None:
+                self.p(stream_ptr)
+            else:
+                skv.step_stage_events(ev)
+                self.p(stream_ptr)
+                skv.step_stage_events(None)
+
+    class PositionalCall:
+        """select_positional -> compact -> attend through the single-stage entry points"""
+        def __init__(self, x, src, cache_len, n_sink, n_recent, dst, o):
+            sink = min(n_sink, cache_len)
+            self.keep = sink + min(n_recent, cache_len - sink)
+            self.idx = idx_buf.view(-1)[: U * self.keep].view(S, H, self.keep)
+            self.a = (x, src, cache_len, n_sink, n_recent, dst, o)
+
+        def run(self, ev):
+            x, src, cache_len, n_sink, n_recent, dst, o = self.a
+            mark = (lambda i: hip.hipEventRecord(ev[i], stream_ptr) if ev[i] else 0) if ev is not None else (lambda i: 0)
+            mark(0)
+            skv.select_positional(shape, cache_len, n_sink, n_recent, self.idx)
+            mark(1)
+            new_len = skv.compact(shape, src[0], src[1], cache_len, self.idx, self.keep, x.k_cur, x.v_cur,
+                                  dst[0], dst[1])
+            mark(2)
+            skv.attend(shape, x.q, dst[0], dst[1], new_len, o)
+            mark(3)
+
+    if variant == "pyramid":   # same mean budget per scale as the drafter/refiner table
+        table = [[0] * K for _ in range(Lyr)]
+        for k in range(1, K + 1):
+            full = W.c_full(cfg, k)
+            b_uni = full if k < cfg.first_compressed_scale else max(1, int(uniform_frac * full + 0.5))
+            for l, b in enumerate(skv.pyramid_budgets(Lyr, b_uni, b_uni // 4 if k >= cfg.first_compressed_scale else b_uni)):
+                table[l][k - 1] = b
     calls, meta = [], []
     lens = [cfg.prefix] * Lyr
     srcs = [prefix[l] for l in range(Lyr)]
+    cur_buf = []
+    if variant == "literal":
+        # read-only start of every pass: the prefix in a buffer with room for the uncompressed scales
+        ks = cfg.first_compressed_scale
+        room = W.c_full(cfg, min(ks, K)) + cfg.n_tokens(min(ks, K))
+        for l in range(Lyr):
+            pair = tuple(torch.empty(S, H, room, d, dtype=dtype, device=dev) for _ in range(2))
+            pair[0][:, :, :cfg.prefix].copy_(prefix[l][0]); pair[1][:, :, :cfg.prefix].copy_(prefix[l][1])
+            cur_buf.append(pair)
     for k in range(1, K + 1):
         n_cur = cfg.n_tokens(k)
+        full = W.c_full(cfg, k)
         for l in range(Lyr):
             x = inputs[(l, k)]
             dst = bufs[l][k % 2]
-            call = skv.PreparedStep(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
-                                    table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
-            calls.append(call)
-            meta.append((l, k, lens[l], call.new_len - n_cur, n_cur))
-            srcs[l], lens[l] = dst, call.new_len
-    stream_ptr = torch.cuda.current_stream().cuda_stream
+            m = dict(layer=l, scale=k, cache_len=lens[l], n_cur=n_cur, score_bytes=0.0)
+            if variant in ("scalekv", "pyramid"):
+                call = skv.PreparedStep(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
+                                        table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
+                keep = call.new_len - n_cur
+                m.update(keep=keep, kv_len=keep + n_cur, new_len=call.new_len,
+                         move_bytes=2.0 * 2.0 * (keep + n_cur) * d * e * U + (4.0 * keep * U if keep < lens[l] else 0))
+                if 0 < keep < lens[l]:
+                    m["score_bytes"] = (lens[l] * d * e + len(windows[k]) * d * e + 4.0 * lens[l]) * U
+                calls.append(LibCall(call))
+                srcs[l], lens[l] = dst, call.new_len
+            elif variant == "literal":
+                # the cache lives in cur_buf[l], which has room for the map; kept rows move to the other buffer
+                cur = cur_buf[l]
+                dst = bufs[l][1] if cur is bufs[l][0] else bufs[l][0]
+                budget = table[l][k - 1] if k >= cfg.first_compressed_scale else full + n_cur
+                call = skv.PreparedAppendFirst(shape, x.q, x.k_cur, x.v_cur, centroids[k], args.pool_w, cur[0], cur[1],
+                                               lens[l], budget, dst[0], dst[1], outs[k], None, ws)
+                assert call.moved == (k >= cfg.first_compressed_scale)
+                total = lens[l] + n_cur
+                m.update(keep=call.keep, kv_len=total, new_len=call.keep,
+                         move_bytes=2.0 * 2.0 * n_cur * d * e * U
+                         + (2.0 * 2.0 * call.keep * d * e * U + 4.0 * call.keep * U if call.moved else 0))
+                calls.append(LibCall(call))
+                lens[l] = call.keep
+                if call.moved:
+                    cur_buf[l] = dst
+            else:
+                b_uni = full if k < cfg.first_compressed_scale else max(1, int(uniform_frac * full + 0.5))
+                n_sink = N_SINK if variant == "sinks" else 0
+                call = PositionalCall(x, srcs[l], lens[l], min(n_sink, b_uni), max(0, b_uni - n_sink), dst, outs[k])
+                keep = call.keep
+                m.update(keep=keep, kv_len=keep + n_cur, new_len=keep + n_cur,
+                         move_bytes=2.0 * 2.0 * (keep + n_cur) * d * e * U + 4.0 * keep * U)
+                calls.append(call)
+                srcs[l], lens[l] = dst, keep + n_cur
+            meta.append(m)
 
     def run_sequence(ev_blocks=None):
-        """the whole multi-scale sequence: one scalekv_step per (scale, layer)"""
+        """the whole multi-scale sequence: one call per (scale, layer)"""
         if ev_blocks is None:
             for call in calls:
-                call(stream_ptr)
+                call.run(None)
         else:
-            armed = False
             for call, ev in zip(calls, ev_blocks):
-                if ev is not None or armed:
-                    skv.step_stage_events(ev)
-                    armed = ev is not None
-                call(stream_ptr)
-            skv.step_stage_events(None)
+                call.run(ev)
 
     n_calls = Lyr * K
     for w in range(args.warmup):
@@ -219,7 +336,9 @@ def main() -> int:
     # stream and give that kernel's average duration for the roofline.
     def is_big(n_cur):
         return n_cur > 128 and dtype == torch.bfloat16 and d == 128
-    ev_steps = [[events.block(5, only=(3, 4)) if is_big(m[4]) else None for m in meta] for _ in range(args.steps)]
+    n_ev = len(stages) + 1
+    ev_steps = [[events.block(n_ev, only=(att, att + 1)) if is_big(m["n_cur"]) else None for m in meta]
+                for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -232,50 +351,52 @@ def main() -> int:
     attend_big = dict(ms=0.0, flops=0.0, launches=0, traffic=0.0, min_bytes=0.0)
     traffic_known = (S, H, d) == (16, 16, 128)
     for s in range(args.steps):
-        for i, (l, k, cache_len, keep, n_cur) in enumerate(meta):
+        for i, m in enumerate(meta):
             ev = ev_steps[s][i]
             if ev is None:
                 continue
-            attend_big["ms"] += events.elapsed_ms(ev[3], ev[4])
-            attend_big["flops"] += 4.0 * n_cur * (keep + n_cur) * d * U
+            n_cur, kv_len = m["n_cur"], m["kv_len"]
+            attend_big["ms"] += events.elapsed_ms(ev[att], ev[att + 1])
+            attend_big["flops"] += 4.0 * n_cur * kv_len * d * U
             attend_big["launches"] += 1
-            attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * (keep + n_cur)) * d * e * U
-            if traffic_known and (n_cur, keep) in ATTEND_PIPE_TRAFFIC:
-                attend_big["traffic"] += ATTEND_PIPE_TRAFFIC[(n_cur, keep)]
+            attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * kv_len) * d * e * U
+            if traffic_known and (n_cur, kv_len - n_cur) in ATTEND_PIPE_TRAFFIC:
+                attend_big["traffic"] += ATTEND_PIPE_TRAFFIC[(n_cur, kv_len - n_cur)]
             else:
                 traffic_known = False
 
     # ---- one more pass, outside the timed region, with an event at every stage boundary:
     # per-stage and per-scale times and the bandwidth of the two streaming stages
-    stage_names = ("score", "select", "compact", "attend")
+    stage_names = stages
     stage_ms = {n: 0.0 for n in stage_names}
     per_scale_ms = {k: 0.0 for k in range(1, K + 1)}
-    per_scale_stage_ms = {k: [0.0] * 4 for k in range(1, K + 1)}
+    per_scale_stage_ms = {k: [0.0] * len(stages) for k in range(1, K + 1)}
     attend_all = dict(ms=0.0, flops=0.0)
     compact_stat = dict(ms=0.0, bytes=0.0)
     score_stat = dict(ms=0.0, bytes=0.0)
     ms_stage_pass = None
+    move_slots = [j for j, n in enumerate(stages) if n in ("compact", "append")]
     if not args.no_stage_pass:
-        ev_all = [events.block(5) for _ in range(n_calls)]
+        ev_all = [events.block(n_ev) for _ in range(n_calls)]
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         run_sequence(ev_all)
         torch.cuda.synchronize()
         ms_stage_pass = (time.perf_counter() - t1) * 1e3
         log(f"instrumented pass (events at every stage boundary): {ms_stage_pass:.2f} ms")
-        for i, (l, k, cache_len, keep, n_cur) in enumerate(meta):
-            ev = ev_all[i]
-            t = [events.elapsed_ms(ev[j], ev[j + 1]) for j in range(4)]
+        for i, m in enumerate(meta):
+            ev, k = ev_all[i], m["scale"]
+            t = [events.elapsed_ms(ev[j], ev[j + 1]) for j in range(len(stages))]
             for j, (n, x) in enumerate(zip(stage_names, t)):
                 stage_ms[n] += x
                 per_scale_stage_ms[k][j] += x
             per_scale_ms[k] += sum(t)
-            attend_all["ms"] += t[3]; attend_all["flops"] += 4.0 * n_cur * (keep + n_cur) * d * U
-            compact_stat["ms"] += t[2]
-            compact_stat["bytes"] += 2.0 * 2.0 * (keep + n_cur) * d * e * U + (4.0 * keep * U if keep < cache_len else 0)
-            if 0 < keep < cache_len:
-                score_stat["ms"] += t[0]
-                score_stat["bytes"] += (cache_len * d * e + len(windows[k]) * d * e + 4.0 * cache_len) * U
+            attend_all["ms"] += t[att]; attend_all["flops"] += 4.0 * m["n_cur"] * m["kv_len"] * d * U
+            compact_stat["ms"] += sum(t[j] for j in move_slots)
+            compact_stat["bytes"] += m["move_bytes"]
+            if m["score_bytes"] > 0 and "score" in stages:
+                score_stat["ms"] += t[stages.index("score")]
+                score_stat["bytes"] += m["score_bytes"]
     events.destroy()
     per_scale_ms = {str(k): v for k, v in per_scale_ms.items()}
 
@@ -295,8 +416,9 @@ def main() -> int:
     score_gbs = score_stat["bytes"] / (score_stat["ms"] * 1e-3) / 1e9 if score_stat["ms"] > 0 else 0.0
 
     result = {
-        "metric": "ScaleKV step ms per 1024^2 image batch (13 scales)" if cfg.name == "2b_1024"
-                  else f"ScaleKV step ms per image batch ({cfg.name})",
+        "metric": ("ScaleKV step ms per 1024^2 image batch (13 scales)" if cfg.name == "2b_1024"
+                   else f"ScaleKV step ms per image batch ({cfg.name})")
+                  + ("" if variant == "scalekv" else f" [variant: {variant}]"),
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if dtype == torch.bfloat16 else "f32", "data": "synthetic",
@@ -304,17 +426,18 @@ def main() -> int:
                                f"({cfg.image_tokens} image tokens, {cfg.prefix}-token prefix), "
                                f"{cfg.n_drafter} drafters at {cfg.drafter_frac:.0%} / {Lyr - cfg.n_drafter} refiners at "
                                f"{cfg.refiner_frac:.0%} per scale, window {cfg.window}",
-                   "calls_per_step": n_calls, "shared_inputs": bool(args.shared_inputs)},
+                   "variant": variant, "calls_per_step": n_calls, "shared_inputs": bool(args.shared_inputs)},
         "roofline": roofline,
         "stage_pass": None if ms_stage_pass is None else {
             "note": "one extra pass outside the timed region with an event at every stage boundary",
+            "stages": list(stages),
             "ms": ms_stage_pass, "stage_ms": stage_ms, "per_scale_ms": per_scale_ms,
             "per_scale_stage_ms": {str(k): [round(x, 4) for x in v] for k, v in per_scale_stage_ms.items()}},
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS},
         "score_hbm": {"achieved": score_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": score_gbs / PEAK_HBM_GBS},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and variant == "scalekv":
         log("timing the CPU oracle on its sample ...")
         del inputs, bufs
         torch.cuda.empty_cache()
