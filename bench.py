@@ -260,6 +260,10 @@ def main() -> int:
             b_uni = full if k < cfg.first_compressed_scale else max(1, int(uniform_frac * full + 0.5))
             for l, b in enumerate(skv.pyramid_budgets(Lyr, b_uni, b_uni // 4 if k >= cfg.first_compressed_scale else b_uni)):
                 table[l][k - 1] = b
+    def is_big(n_cur):
+        """shapes that take the pipelined attention kernel, which also appends the map's K/V itself"""
+        return n_cur > 128 and dtype == torch.bfloat16 and d == 128
+
     calls, meta = [], []
     lens = [cfg.prefix] * Lyr
     srcs = [prefix[l] for l in range(Lyr)]
@@ -278,13 +282,16 @@ def main() -> int:
         for l in range(Lyr):
             x = inputs[(l, k)]
             dst = bufs[l][k % 2]
-            m = dict(layer=l, scale=k, cache_len=lens[l], n_cur=n_cur, score_bytes=0.0)
+            m = dict(layer=l, scale=k, cache_len=lens[l], n_cur=n_cur, score_bytes=0.0, append_in_attend=0.0)
+            append_bytes = 2.0 * 2.0 * n_cur * d * e * U   # K and V, read + write
             if variant in ("scalekv", "pyramid"):
                 call = skv.PreparedStep(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
                                         table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
                 keep = call.new_len - n_cur
                 m.update(keep=keep, kv_len=keep + n_cur, new_len=call.new_len,
-                         move_bytes=2.0 * 2.0 * (keep + n_cur) * d * e * U + (4.0 * keep * U if keep < lens[l] else 0))
+                         move_bytes=2.0 * 2.0 * keep * d * e * U + (4.0 * keep * U if keep < lens[l] else 0)
+                         + (0.0 if is_big(n_cur) else append_bytes),
+                         append_in_attend=append_bytes if is_big(n_cur) else 0.0)
                 if 0 < keep < lens[l]:
                     m["score_bytes"] = (lens[l] * d * e + len(windows[k]) * d * e + 4.0 * lens[l]) * U
                 calls.append(LibCall(call))
@@ -299,8 +306,9 @@ def main() -> int:
                 assert call.moved == (k >= cfg.first_compressed_scale)
                 total = lens[l] + n_cur
                 m.update(keep=call.keep, kv_len=total, new_len=call.keep,
-                         move_bytes=2.0 * 2.0 * n_cur * d * e * U
-                         + (2.0 * 2.0 * call.keep * d * e * U + 4.0 * call.keep * U if call.moved else 0))
+                         move_bytes=(0.0 if is_big(n_cur) else append_bytes)
+                         + (2.0 * 2.0 * call.keep * d * e * U + 4.0 * call.keep * U if call.moved else 0),
+                         append_in_attend=append_bytes if is_big(n_cur) else 0.0)
                 calls.append(LibCall(call))
                 lens[l] = call.keep
                 if call.moved:
@@ -334,8 +342,6 @@ def main() -> int:
     # Timed region: K passes of the sequence.  The only events inside it bracket the launches
     # of the dominant kernel (the pipelined bf16 attention, n_cur > 128); they sit on the launch
     # stream and give that kernel's average duration for the roofline.
-    def is_big(n_cur):
-        return n_cur > 128 and dtype == torch.bfloat16 and d == 128
     n_ev = len(stages) + 1
     ev_steps = [[events.block(n_ev, only=(att, att + 1)) if is_big(m["n_cur"]) else None for m in meta]
                 for _ in range(args.steps)]
@@ -359,7 +365,7 @@ def main() -> int:
             attend_big["ms"] += events.elapsed_ms(ev[att], ev[att + 1])
             attend_big["flops"] += 4.0 * n_cur * kv_len * d * U
             attend_big["launches"] += 1
-            attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * kv_len) * d * e * U
+            attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * kv_len) * d * e * U + m["append_in_attend"]
             if traffic_known and (n_cur, kv_len - n_cur) in ATTEND_PIPE_TRAFFIC:
                 attend_big["traffic"] += ATTEND_PIPE_TRAFFIC[(n_cur, kv_len - n_cur)]
             else:

@@ -379,14 +379,23 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                   "select launch");
   }
   SCALEKV_HIP(mark(2), "event record");
+  // The pipelined attention kernel reads the map's own K/V from k_cur/v_cur and copies them
+  // behind the kept rows itself (it is bound by the matrix pipe, the copy by the HBM, so the
+  // two overlap); for the other shapes the compaction kernel appends them.
+  const bool fused_append = attend_uses_pipe(shape->dtype, shape->head_dim, n_cur);
   SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
-                             view(k_src), view(v_src), idx, keep, k_cur, v_cur, n_cur, view(k_dst),
-                             view(v_dst), st),
+                             view(k_src), view(v_src), idx, keep, k_cur, v_cur,
+                             fused_append ? 0 : n_cur, view(k_dst), view(v_dst), st),
               "compact launch");
   SCALEKV_HIP(mark(3), "event record");
-  SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_cur,
-                            view(k_dst), view(v_dst), keep + n_cur, resolve_scale(shape), out, st),
-              "attend launch");
+  if (fused_append)
+    SCALEKV_HIP(launch_attend_pipe(U, shape->n_head, q, n_cur, view(k_dst), view(v_dst), keep, k_cur,
+                                   v_cur, n_cur, true, resolve_scale(shape), out, st),
+                "attend launch");
+  else
+    SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_cur,
+                              view(k_dst), view(v_dst), keep + n_cur, resolve_scale(shape), out, st),
+                "attend launch");
   SCALEKV_HIP(mark(4), "event record");
   if (new_len_out) *new_len_out = keep + n_cur;
   return SCALEKV_OK;
@@ -502,8 +511,10 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
   const int U = shape->n_seq * shape->n_head;
   const int d = shape->head_dim;
   SCALEKV_HIP(mark(0), "event record");
-  // 1. the map's K/V join the cache: rows [cache_len, cache_len + n_cur) of every unit
-  {
+  // 1. the map's K/V join the cache: rows [cache_len, cache_len + n_cur) of every unit (the
+  //    pipelined attention kernel does this itself, overlapped with its own work)
+  const bool fused_append = attend_uses_pipe(shape->dtype, d, n_cur);
+  if (!fused_append) {
     const long long tail = (long long)cache_len * d * elem_bytes(shape);
     KvView kt{static_cast<const char*>(k_cache->ptr) + tail, k_cache->seq_stride,
               k_cache->head_stride};
@@ -515,9 +526,14 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
   }
   SCALEKV_HIP(mark(1), "event record");
   // 2. the map attends over history and itself
-  SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, d, q, n_cur, view(k_cache),
-                            view(v_cache), len, resolve_scale(shape), out, st),
-              "attend launch");
+  if (fused_append)
+    SCALEKV_HIP(launch_attend_pipe(U, shape->n_head, q, n_cur, view(k_cache), view(v_cache), cache_len,
+                                   k_cur, v_cur, n_cur, true, resolve_scale(shape), out, st),
+                "attend launch");
+  else
+    SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, d, q, n_cur, view(k_cache),
+                              view(v_cache), len, resolve_scale(shape), out, st),
+                "attend launch");
   SCALEKV_HIP(mark(2), "event record");
   if (keep_out) *keep_out = keep;
   if (moved_out) *moved_out = moves ? 1 : 0;

@@ -433,8 +433,9 @@ hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q,
   const uint16_t* vp = (const uint16_t*)v.ptr;
   uint16_t* op = (uint16_t*)out;
   if (d == 128) {
-    if (n_q > 128)
-      return launch_attend_pipe(n_unit, n_head, q, n_q, k, v, kv_len, sm_scale, out, stream);
+    if (attend_uses_pipe(dtype, d, n_q))
+      return launch_attend_pipe(n_unit, n_head, q, n_q, k, v, kv_len, nullptr, nullptr, 0, false,
+                                sm_scale, out, stream);
     return launch_mfma<128, 1>(dim3((n_q + 127) / 128, n_unit), stream, qp, n_q, kp, k, vp, v,
                                kv_len, n_head, scale_log2e, op);
   }

@@ -42,6 +42,14 @@
 //
 // Workgroups of one (sequence, head) unit are numbered so that they land on the
 // same XCD and share its L2 while they stream the same K/V.
+//
+// Two key segments.  The keys are the first len1 rows of a cache followed by len2
+// rows of a dense tensor (the current map's own K/V); each segment is walked in tiles
+// of its own, so at most one ragged tile per segment is masked.  When asked to, every
+// workgroup also copies its share of the second segment behind the first in the cache
+// (rows len1 .. len1+len2-1): the append of the pruning step, done here because this
+// kernel is bound by the matrix pipe and leaves the HBM idle, while a separate copy
+// kernel would be bound by the HBM and leave the matrix pipe idle.
 #include "common.h"
 
 namespace scalekv {
@@ -51,6 +59,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
@@ -91,11 +100,11 @@ __device__ __forceinline__ float both_halves_sum(float x) {
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t* __restrict__ k,
-                        long long k_seq_stride, long long k_head_stride,
-                        const uint16_t* __restrict__ v, long long v_seq_stride,
-                        long long v_head_stride, int kv_len, int n_head, int n_qtile,
-                        int n_wg, float scale_log2e, uint16_t* __restrict__ out) {
+void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, long long k_seq_stride,
+                        long long k_head_stride, uint16_t* v, long long v_seq_stride,
+                        long long v_head_stride, int len1, const uint16_t* __restrict__ k2,
+                        const uint16_t* __restrict__ v2, int len2, int append, int n_head,
+                        int n_qtile, int n_wg, float scale_log2e, uint16_t* __restrict__ out) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* const k_lds = smem;
   unsigned char* const v_lds = smem + kStages * kTileBytes;
@@ -115,6 +124,10 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
   const uint16_t* qu = q + (long long)unit * n_q * D;
   const unsigned char* ku = (const unsigned char*)(k + seq * k_seq_stride + head * k_head_stride);
   const unsigned char* vu = (const unsigned char*)(v + seq * v_seq_stride + head * v_head_stride);
+  const unsigned char* k2u = (const unsigned char*)(k2 + (long long)unit * len2 * D);
+  const unsigned char* v2u = (const unsigned char*)(v2 + (long long)unit * len2 * D);
+  const int n_tile1 = (len1 + TN - 1) / TN;
+  const int n_tile = n_tile1 + (len2 + TN - 1) / TN;
 
   // ---- tile loader: per thread 4 K vectors and 4 V vectors of 16 bytes.
   // Instruction p of wave w fills LDS rows 16w + 4p .. +3 (64 lanes x 16 B = 4 rows);
@@ -144,14 +157,19 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
   auto lds_addr = [](const unsigned char* p) -> unsigned {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
   };
+  // LDS byte addresses of this wave's 16 rows in stage 0 (wave-uniform, kept in scalar registers)
+  const unsigned k_lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(k_lds + (16 * wave) * kRowBytes));
+  const unsigned v_lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(v_lds + (16 * wave) * kRowBytes));
   auto issue_tile = [&](int tile) {
-    const unsigned ks = __builtin_amdgcn_readfirstlane(
-        lds_addr(k_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes));
-    const unsigned vs = __builtin_amdgcn_readfirstlane(
-        lds_addr(v_lds + (tile % kStages) * kTileBytes + (16 * wave) * kRowBytes));
-    const unsigned char* kt = ku + (long long)tile * kTileBytes;  // wave-uniform tile base
-    const unsigned char* vt = vu + (long long)tile * kTileBytes;
-    if ((tile + 1) * TN <= kv_len) {
+    const unsigned ks = k_lds_wave + (tile % kStages) * kTileBytes;
+    const unsigned vs = v_lds_wave + (tile % kStages) * kTileBytes;
+    // wave-uniform tile base and number of valid rows, in whichever segment the tile lies
+    const bool second = tile >= n_tile1;
+    const int lt = second ? tile - n_tile1 : tile;
+    const unsigned char* kt = (second ? k2u : ku) + (long long)lt * kTileBytes;
+    const unsigned char* vt = (second ? v2u : vu) + (long long)lt * kTileBytes;
+    const int valid = (second ? len2 : len1) - lt * TN;
+    if (valid >= TN) {
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         dma16(kt, ld_kofs[p], ks + 4 * p * kRowBytes);
@@ -160,7 +178,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
     } else {
       // ragged last tile: rows past the end re-read the last valid row (finite data that
       // the mask turns into zero weight)
-      const int last_row = kv_len - 1 - tile * TN;
+      const int last_row = valid - 1;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const int back = max(ld_row[p] - last_row, 0) * kRowBytes;
@@ -247,13 +265,14 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
     for (int sl = 0; sl < 8; ++sl) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sl], qf[sl], s, 0, 0, 0);
     return s;
   };
-  // softmax of the block's scores (register r = key 16(r/8) + 8h + r%8 of the block; `mask`
-  // hides keys at or beyond kv_len) followed by O^T += V^T P^T
-  auto softmax_pv = [&](f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key) {
+  // softmax of the block's scores (register r = key 16(r/8) + 8h + r%8 of the block, which
+  // starts at row first_key of its tile; `mask` hides rows at or beyond `valid`) followed by
+  // O^T += V^T P^T
+  auto softmax_pv = [&](f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key, int valid) {
     if (mask) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (first_key + 16 * (r / 8) + 8 * h + (r % 8) >= kv_len) s[r] = -INFINITY;
+        if (first_key + 16 * (r / 8) + 8 * h + (r % 8) >= valid) s[r] = -INFINITY;
     }
     float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
@@ -284,7 +303,6 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
   // finished every LDS read of the tile (so its stage may be refilled) and has waited for
   // its share of the next tile (so that tile may be read).  The fences stop the compiler
   // from sinking the requests back next to their uses.
-  const int n_tile = (kv_len + TN - 1) / TN;
   constexpr int kHalf = 32 * kRowBytes;
   bf16x8 kf[8], vf[2][4];
   issue_tile(0);
@@ -296,7 +314,8 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
   // next tile's stage; in the main loop they are constants and fold into the LDS
   // instructions' offset fields.
   auto tile = [&](int t, int ofs, int next_ofs) {
-    const bool mask = (t + 1) * TN > kv_len;
+    const int valid = t < n_tile1 ? len1 - t * TN : len2 - (t - n_tile1) * TN;
+    const bool mask = valid < TN;
     // ---- first block of the tile
     fetch_vt(vf, ofs);
     __builtin_amdgcn_sched_barrier(0);
@@ -304,7 +323,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
     __builtin_amdgcn_sched_barrier(0);
     fetch_k(kf, ofs + kHalf);
     __builtin_amdgcn_sched_barrier(0);
-    softmax_pv(s, vf, mask, t * TN);
+    softmax_pv(s, vf, mask, 0, valid);
     // ---- second block
     __builtin_amdgcn_sched_barrier(0);
     fetch_vt(vf, ofs + kHalf);
@@ -318,7 +337,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
       fetch_k(kf, next_ofs);
     }
     __builtin_amdgcn_sched_barrier(0);
-    softmax_pv(s, vf, mask, t * TN + 32);
+    softmax_pv(s, vf, mask, 32, valid);
   };
   int t = 0;
   for (; t + 1 < n_tile; t += 2) {  // t even: stage 0 then stage 1
@@ -347,12 +366,43 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, const uint16_t*
         }
     }
   }
+
+  // ---- append: this workgroup's share of the second segment goes behind the first, as 16-byte
+  // vectors.  Done last, when the accumulators are dead and a thread can hold its whole share
+  // (16 vectors when the share is 128 rows) in flight at once; the other workgroup on the
+  // compute unit keeps the matrix pipe busy meanwhile.
+  if (append) {
+    const int per = (len2 + n_qtile - 1) / n_qtile;
+    const int row0 = min(qtile * per, len2);
+    const int n_vec = min(per, len2 - row0) * (kRowBytes / 16);  // per tensor
+    const u32x4* ks = (const u32x4*)(k2u + (long long)row0 * kRowBytes);
+    const u32x4* vs = (const u32x4*)(v2u + (long long)row0 * kRowBytes);
+    u32x4* kd = (u32x4*)(const_cast<unsigned char*>(ku) + (long long)(len1 + row0) * kRowBytes);
+    u32x4* vd = (u32x4*)(const_cast<unsigned char*>(vu) + (long long)(len1 + row0) * kRowBytes);
+    for (int i0 = 0; i0 < n_vec; i0 += 8 * 256) {
+      u32x4 a[8], b[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * 256 + tid;
+        if (i < n_vec) { a[u] = ks[i]; b[u] = vs[i]; }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * 256 + tid;
+        if (i < n_vec) {
+          __builtin_nontemporal_store(a[u], kd + i);
+          __builtin_nontemporal_store(b[u], vd + i);
+        }
+      }
+    }
+  }
 }
 
 }  // namespace
 
 hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
-                              int kv_len, float sm_scale, void* out, hipStream_t stream) {
+                              int len1, const void* k2, const void* v2, int len2, bool append,
+                              float sm_scale, void* out, hipStream_t stream) {
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)attend_pipe_kernel,
@@ -364,9 +414,10 @@ hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, Kv
   const int n_qtile = (n_q + BM - 1) / BM;
   const int n_wg = n_qtile * n_unit;
   hipLaunchKernelGGL(attend_pipe_kernel, dim3(n_wg), dim3(256), kLdsBytes, stream,
-                     (const uint16_t*)q, n_q, (const uint16_t*)k.ptr, k.seq_stride, k.head_stride,
-                     (const uint16_t*)v.ptr, v.seq_stride, v.head_stride, kv_len, n_head, n_qtile,
-                     n_wg, scale_log2e, (uint16_t*)out);
+                     (const uint16_t*)q, n_q, (uint16_t*)const_cast<void*>(k.ptr), k.seq_stride,
+                     k.head_stride, (uint16_t*)const_cast<void*>(v.ptr), v.seq_stride, v.head_stride,
+                     len1, (const uint16_t*)k2, (const uint16_t*)v2, len2, append ? 1 : 0, n_head,
+                     n_qtile, n_wg, scale_log2e, (uint16_t*)out);
   return hipGetLastError();
 }
 

@@ -71,9 +71,15 @@ hipError_t launch_compact(int dtype, int n_seq, int n_head, int d, KvView k_src,
 hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q, int n_q, KvView k,
                          KvView v, int kv_len, float sm_scale, void* out, hipStream_t stream);
 
-// bf16, head_dim 128 only: the pipelined kernel used when n_q is large
+// bf16, head_dim 128 only: the pipelined kernel used when n_q is large.  Keys and values are the
+// first len1 rows of the caches k, v followed by the len2 rows of the dense tensors k2, v2
+// ([U, len2, d]; may be NULL when len2 == 0).  With `append` the kernel also copies k2, v2 into
+// rows [len1, len1 + len2) of the caches, which must have room for them.
 hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
-                              int kv_len, float sm_scale, void* out, hipStream_t stream);
+                              int len1, const void* k2, const void* v2, int len2, bool append,
+                              float sm_scale, void* out, hipStream_t stream);
+// whether launch_attend would take the pipelined kernel for this shape
+inline bool attend_uses_pipe(int dtype, int d, int n_q) { return dtype == 1 && d == 128 && n_q > 128; }
 
 // ---- device helpers ----
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
