@@ -35,10 +35,18 @@
 // middle of tile t's second block, which is also the point from which tile t+1 may
 // be read.  LDS operands are requested one phase ahead of the MFMAs that use them.
 //
-// Softmax.  Exponent offsets m_run are only moved (and O, l rescaled) when some
-// row max grew by more than kRescaleThreshold in log2 units; until then exp2
-// arguments stay <= the threshold, which fp32 and bf16 hold without loss.  The row
-// sum adds the bf16-rounded probabilities, the very numbers the MFMA multiplies by.
+// Softmax.  The exponent offset m_run of a query row is taken from the row's maximum
+// over the first tile and then left alone: every later probability is exp2 of
+// (score - m_run), whatever its size, and the row sum adds the bf16-rounded
+// probabilities, the very numbers the MFMA multiplies by.  No running maximum is
+// formed (it costs a sixth of the vector instructions of a block).  This is exact as
+// long as nothing overflows, and fp32 / bf16 carry 2^127: a lane only checks that its
+// share of a block's row sum stays below 2^40 and records a failure in a scalar mask.
+// If any wave of the workgroup recorded one (scores more than 27 natural units above
+// the first tile's maximum: not seen with attention-like inputs, forced by the tests),
+// the workgroup discards its result and repeats the whole pass with the classical
+// scheme: running maximum per block, offsets moved (and O, l rescaled) when some row
+// maximum grew by more than kRescaleThreshold in log2 units.
 //
 // Workgroups of one (sequence, head) unit are numbered so that they land on the
 // same XCD and share its L2 while they stream the same K/V.
@@ -50,6 +58,8 @@
 // (rows len1 .. len1+len2-1): the append of the pruning step, done here because this
 // kernel is bound by the matrix pipe and leaves the HBM idle, while a separate copy
 // kernel would be bound by the HBM and leave the matrix pipe idle.
+#include <type_traits>
+
 #include "common.h"
 
 namespace scalekv {
@@ -71,6 +81,7 @@ constexpr int kTileBytes = TN * kRowBytes;  // 16 KB
 constexpr int kStages = 2;
 constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // K stages then V stages: 64 KB
 constexpr float kRescaleThreshold = 8.f;
+constexpr float kBlockSumLimit = 1099511627776.f;  // 2^40: largest row-sum share a block may add unchecked
 constexpr int kXcds = 8;
 
 __device__ __forceinline__ int pi32(int i) {  // swap bits 2 and 3
@@ -97,6 +108,44 @@ __device__ __forceinline__ float both_halves_sum(float x) {
   const uint32_t u = __float_as_uint(x);
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// One 16-byte-per-lane transfer from global memory straight into LDS: lane l's vector comes
+// from base + voff + IMM and lands at LDS byte lds_addr + IMM + 16 l (the instruction's
+// immediate offset applies to both addresses).  The request is written in
+// assembly on purpose: the compiler, when it knows about a global->LDS transfer, waits for
+// it before the next LDS read of the same array, which would serialise the transfer of tile
+// t+1 with the consumption of tile t.  Here the only wait is the explicit one in front of the
+// barrier that publishes the tile.
+template <int IMM>
+__device__ __forceinline__ void dma16(const unsigned char* base_uniform, unsigned voff,
+                                      unsigned lds_addr_uniform) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2 offset:%3"
+      :
+      : "s"(lds_addr_uniform), "v"(voff), "s"(base_uniform), "n"(IMM)
+      : "m0", "memory");
+}
+
+// The same with the lane's offset formed on the spot as (chunk ^ flip) + row: the K tile's
+// chunk swizzle differs between a lane's four transfers by an XOR, and forming it here keeps
+// the compiler from holding four precomputed offsets in registers through the main loop.
+template <int IMM>
+__device__ __forceinline__ void dma16_xor(const unsigned char* base_uniform, unsigned row_part,
+                                          unsigned chunk_part, unsigned flip_uniform,
+                                          unsigned lds_addr_uniform) {
+  unsigned voff;
+  asm volatile(
+      "v_xad_u32 %0, %2, %3, %1\n\t"
+      "s_mov_b32 m0, %4\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %5 offset:%6"
+      : "=&v"(voff)
+      : "v"(row_part), "v"(chunk_part), "s"(flip_uniform), "s"(lds_addr_uniform),
+        "s"(base_uniform), "n"(IMM)
+      : "m0", "memory");
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -131,36 +180,22 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
 
   // ---- tile loader: per thread 4 K vectors and 4 V vectors of 16 bytes.
   // Instruction p of wave w fills LDS rows 16w + 4p .. +3 (64 lanes x 16 B = 4 rows);
-  // the lane that lands in chunk slot s of row r fetches global chunk s ^ f(r).
-  int ld_row[4];
-  unsigned ld_kofs[4], ld_vofs[4];  // byte offset of this lane's vector inside a full tile
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int r = 16 * wave + 4 * p + (lane >> 4);
-    ld_row[p] = r;
-    ld_kofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ (r & 15));
-    ld_vofs[p] = r * kRowBytes + 16 * ((lane & 15) ^ ((r & 3) << 2));
-  }
-  // The request itself is written in assembly on purpose: the compiler, when it knows
-  // about a global->LDS transfer, waits for it before the next LDS read of the same array,
-  // which would serialise the transfer of tile t+1 with the consumption of tile t.  Here
-  // the only wait is the explicit one in front of the barrier that publishes the tile.
-  auto dma16 = [&](const unsigned char* base_uniform, unsigned voff, unsigned lds_addr_uniform) {
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2"
-        :
-        : "s"(lds_addr_uniform), "v"(voff), "s"(base_uniform)
-        : "m0", "memory");
-  };
+  // the lane that lands in chunk slot s of row r fetches global chunk s ^ f(r), with
+  // f(r) = r & 15 for K and (r & 3) << 2 for V.  For this lane r = r0 + 4p with r0 & 15 =
+  // lane >> 4 < 4, so its K chunk is c0 ^ 4p with c0 = (lane & 15) ^ (lane >> 4) and its V
+  // chunk does not depend on p: one register pair serves all four instructions, the rest
+  // (1024 p bytes) rides in the instruction's immediate offset.
+  const int ld_row0 = 16 * wave + (lane >> 4);
+  const unsigned ld_krow = ld_row0 * kRowBytes;                          // K: row part
+  const unsigned ld_kchunk = 16 * ((lane & 15) ^ (lane >> 4));           // K: chunk part for p = 0
+  const unsigned ld_vofs = ld_row0 * kRowBytes + 16 * ((lane & 15) ^ ((lane >> 4) << 2));
   auto lds_addr = [](const unsigned char* p) -> unsigned {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) unsigned char*)p;
   };
   // LDS byte addresses of this wave's 16 rows in stage 0 (wave-uniform, kept in scalar registers)
   const unsigned k_lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(k_lds + (16 * wave) * kRowBytes));
   const unsigned v_lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(v_lds + (16 * wave) * kRowBytes));
-  auto issue_tile = [&](int tile) {
+  auto issue_tile = [&](int tile) __attribute__((always_inline)) {
     const unsigned ks = k_lds_wave + (tile % kStages) * kTileBytes;
     const unsigned vs = v_lds_wave + (tile % kStages) * kTileBytes;
     // wave-uniform tile base and number of valid rows, in whichever segment the tile lies
@@ -170,20 +205,25 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     const unsigned char* vt = (second ? v2u : vu) + (long long)lt * kTileBytes;
     const int valid = (second ? len2 : len1) - lt * TN;
     if (valid >= TN) {
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        dma16(kt, ld_kofs[p], ks + 4 * p * kRowBytes);
-        dma16(vt, ld_vofs[p], vs + 4 * p * kRowBytes);
-      }
+      // the immediate offset moves the LDS destination along with the global source, which
+      // is exactly the 4 rows between a lane's consecutive transfers
+      dma16_xor<0>(kt, ld_krow, ld_kchunk, 0u, ks);
+      dma16<0>(vt, ld_vofs, vs);
+      dma16_xor<1024>(kt, ld_krow, ld_kchunk, 64u, ks);
+      dma16<1024>(vt, ld_vofs, vs);
+      dma16_xor<2048>(kt, ld_krow, ld_kchunk, 128u, ks);
+      dma16<2048>(vt, ld_vofs, vs);
+      dma16_xor<3072>(kt, ld_krow, ld_kchunk, 192u, ks);
+      dma16<3072>(vt, ld_vofs, vs);
     } else {
       // ragged last tile: rows past the end re-read the last valid row (finite data that
       // the mask turns into zero weight)
       const int last_row = valid - 1;
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        const int back = max(ld_row[p] - last_row, 0) * kRowBytes;
-        dma16(kt, ld_kofs[p] - back, ks + 4 * p * kRowBytes);
-        dma16(vt, ld_vofs[p] - back, vs + 4 * p * kRowBytes);
+        const int back = max(ld_row0 + 4 * p - last_row, 0) * kRowBytes;
+        dma16<0>(kt, ld_krow + (ld_kchunk ^ (64 * p)) + 1024 * p - back, ks + 4 * p * kRowBytes);
+        dma16<0>(vt, ld_vofs + 1024 * p - back, vs + 4 * p * kRowBytes);
       }
     }
   };
@@ -216,12 +256,9 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   }
 
   f32x16 o[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m_run = -INFINITY;  // exponent offset
-  float l_run = 0.f;        // this lane's share of the row sum
+  float m_run;  // exponent offset
+  float l_run;  // this lane's share of the row sum
+  unsigned long long overflowed = 0;  // lanes whose block sum left the unchecked range
 
   auto load_k = [&](int ofs, int sl) -> bf16x8 { return *(const bf16x8*)(k_lds + ofs + k_ofs[sl]); };
   auto load_vt = [&](int ofs, int sl, int db) -> bf16x8 {
@@ -268,28 +305,36 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   // softmax of the block's scores (register r = key 16(r/8) + 8h + r%8 of the block, which
   // starts at row first_key of its tile; `mask` hides rows at or beyond `valid`) followed by
   // O^T += V^T P^T
-  auto softmax_pv = [&](f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key, int valid) {
+  // `tracked` (a std::bool_constant): follow the running maximum; otherwise keep m_run and
+  // only watch for overflow.
+  auto softmax_pv = [&](auto tracked, f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key,
+                        int valid) __attribute__((always_inline)) {
     if (mask) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (first_key + 16 * (r / 8) + 8 * h + (r % 8) >= valid) s[r] = -INFINITY;
     }
-    float mx = max3(s[0], s[1], s[2]);
+    if constexpr (decltype(tracked)::value) {
+      float mx = max3(s[0], s[1], s[2]);
 #pragma unroll
-    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
-    mx = both_halves_max(fmaxf(mx, s[15]));
-    if (__builtin_amdgcn_ballot_w64((mx - m_run) * scale_log2e > kRescaleThreshold) != 0) {
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
-      m_run = m_new;
-      l_run *= alpha;
+      for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
+      mx = both_halves_max(fmaxf(mx, s[15]));
+      if (__builtin_amdgcn_ballot_w64((mx - m_run) * scale_log2e > kRescaleThreshold) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+        m_run = m_new;
+        l_run *= alpha;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      }
     }
     bf16x8 pf[2];
-    l_run += exps(s, m_run * scale_log2e, pf);
+    const float rs = exps(s, m_run * scale_log2e, pf);
+    if constexpr (!decltype(tracked)::value)
+      overflowed |= __builtin_amdgcn_ballot_w64(!(rs <= kBlockSumLimit));  // catches NaN too
+    l_run += rs;
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl)
 #pragma unroll
@@ -305,15 +350,10 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   // from sinking the requests back next to their uses.
   constexpr int kHalf = 32 * kRowBytes;
   bf16x8 kf[8], vf[2][4];
-  issue_tile(0);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  if (n_tile > 1) issue_tile(1);
-  fetch_k(kf, 0);
   // One tile (two blocks).  `ofs` / `next_ofs` are the byte offsets of this tile's and the
   // next tile's stage; in the main loop they are constants and fold into the LDS
   // instructions' offset fields.
-  auto tile = [&](int t, int ofs, int next_ofs) {
+  auto tile = [&](auto tracked, int t, int ofs, int next_ofs) __attribute__((always_inline)) {
     const int valid = t < n_tile1 ? len1 - t * TN : len2 - (t - n_tile1) * TN;
     const bool mask = valid < TN;
     // ---- first block of the tile
@@ -323,7 +363,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     __builtin_amdgcn_sched_barrier(0);
     fetch_k(kf, ofs + kHalf);
     __builtin_amdgcn_sched_barrier(0);
-    softmax_pv(s, vf, mask, 0, valid);
+    softmax_pv(tracked, s, vf, mask, 0, valid);
     // ---- second block
     __builtin_amdgcn_sched_barrier(0);
     fetch_vt(vf, ofs + kHalf);
@@ -337,14 +377,33 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
       fetch_k(kf, next_ofs);
     }
     __builtin_amdgcn_sched_barrier(0);
-    softmax_pv(s, vf, mask, 32, valid);
+    softmax_pv(tracked, s, vf, mask, 32, valid);
   };
-  int t = 0;
-  for (; t + 1 < n_tile; t += 2) {  // t even: stage 0 then stage 1
-    tile(t, 0, kTileBytes);
-    tile(t + 1, kTileBytes, 0);
-  }
-  if (t < n_tile) tile(t, 0, kTileBytes);
+  // One pass over all tiles.  The first tile always follows its maxima: that is where
+  // m_run comes from.
+  auto pass = [&](auto tracked) __attribute__((always_inline)) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+    issue_tile(0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (n_tile > 1) issue_tile(1);
+    fetch_k(kf, 0);
+    tile(std::true_type{}, 0, 0, kTileBytes);
+    int t = 1;
+    for (; t + 1 < n_tile; t += 2) {  // t odd: stage 1 then stage 0
+      tile(tracked, t, kTileBytes, 0);
+      tile(tracked, t + 1, 0, kTileBytes);
+    }
+    if (t < n_tile) tile(tracked, t, kTileBytes, 0);
+  };
+  pass(std::false_type{});
+  // every wave has left its last tile when the votes are in, so the stages may be refilled
+  if (__syncthreads_or(overflowed != 0)) pass(std::true_type{});
 
   // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
   {

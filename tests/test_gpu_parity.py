@@ -157,6 +157,44 @@ def test_attend_matches_oracle(dtype, d, n_q, kv_len):
     _note(f"  max {mx:.2e} mean {mean:.2e}")
 
 
+@pytest.mark.parametrize("where", ["late_in_cache", "in_current_map", "second_tile", "some_rows_only"])
+def test_attend_scores_far_above_the_first_tile(where):
+    # Keys whose scores sit far above everything in the first 64 rows: exp2 of their distance to
+    # the first tile's maximum leaves the range the kernel adds up unchecked (and, for the larger
+    # gaps, fp32 altogether), so the workgroup has to fall back to the running-maximum scheme.
+    S, H, d, n_q, len1, len2 = 1, 2, 128, 300, 400, 300
+    dtype = torch.bfloat16
+    _note(f"attend overflow fallback: {where}")
+    shape = skv.Shape(S, H, d, dtype)
+    q = _rand(40, (S, H, n_q, d), dtype)
+    ks, vs = _rand(41, (S, H, len1 + len2, d), dtype, 0.05), _rand(42, (S, H, len1 + len2, d), dtype)
+    row = {"late_in_cache": len1 - 3, "in_current_map": len1 + 170, "second_tile": 70, "some_rows_only": 333}[where]
+    gain = {"late_in_cache": 8.0, "in_current_map": 30.0, "second_tile": 3.0, "some_rows_only": 6.0}[where]
+    if where == "some_rows_only":       # only queries 5..9 see the large scores
+        ks[:, :, row] = (q[:, :, 5].float() * gain).to(dtype)
+        q[:, :, 6:10] = q[:, :, 5:6]
+    else:                               # every query does: key = gain * mean direction of the queries
+        q = (q.float() + 1.0).to(dtype)
+        ks[:, :, row] = gain
+    kc, vc = ks[:, :, len1:].contiguous(), vs[:, :, len1:].contiguous()
+    out = torch.full((S, H, n_q, d), float("nan"), dtype=dtype, device=DEV)
+    skv.attend(shape, q.to(DEV), ks.to(DEV), vs.to(DEV), len1 + len2, out)       # one segment
+    torch.cuda.synchronize()
+    ref = oracle.attend(units(q), units(ks), units(vs))
+    check_output(out, ref, dtype, f"attend {where}")
+    # the same keys as cache + current map through the step (budget = len1 keeps every cached row):
+    # two key segments, and the kernel appends the map's K/V itself
+    kd = torch.zeros(S, H, len1 + len2 + 2, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+    out2 = torch.full_like(out, float("nan"))
+    new_len = skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), [0], ks[:, :, :len1].contiguous().to(DEV),
+                       vs[:, :, :len1].contiguous().to(DEV), len1, len1, kd, vd, out2, None, None)
+    torch.cuda.synchronize()
+    assert new_len == len1 + len2
+    assert torch.equal(kd[:, :, :new_len].cpu(), ks) and torch.equal(vd[:, :, :new_len].cpu(), vs)
+    assert torch.all(kd[:, :, new_len:] == 0) and torch.all(vd[:, :, new_len:] == 0)
+    check_output(out2, ref, dtype, f"step {where}")
+
+
 def test_attend_closed_forms_on_gpu():
     S, H, d, n_q, kv = 1, 2, 128, 140, 260
     dtype = torch.bfloat16
