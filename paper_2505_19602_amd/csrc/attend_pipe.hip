@@ -310,9 +310,12 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   auto softmax_pv = [&](auto tracked, f32x16& s, const bf16x8 (&vf)[2][4], bool mask, int first_key,
                         int valid) __attribute__((always_inline)) {
     if (mask) {
+      // (the lane half is taken from the lane number on the spot, so that the sixteen key
+      // indices of this rarely taken branch are not kept in registers through the main loop)
+      const int half = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) >> 5;
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (first_key + 16 * (r / 8) + 8 * h + (r % 8) >= valid) s[r] = -INFINITY;
+        if (first_key + 16 * (r / 8) + 8 * half + (r % 8) >= valid) s[r] = -INFINITY;
     }
     if constexpr (decltype(tracked)::value) {
       float mx = max3(s[0], s[1], s[2]);
