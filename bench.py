@@ -411,6 +411,45 @@ def main() -> int:
                 if k == K:
                     score_last["ms"] += t[stages.index("score")]
                     score_last["bytes"] += m["score_bytes"]
+    # ---- the two streaming / matrix kernels on their own, at the last scale's drafter shape, outside
+    # the timed region: scalekv_compact doing its whole job (gather + append in one kernel, as the
+    # single-stage entry point does) and scalekv_attend over one segment with nothing else to carry
+    standalone = None
+    if not args.no_stage_pass and variant == "scalekv" and dtype == torch.bfloat16:
+        last = max((m for m in meta if m["scale"] == K), key=lambda m: m["keep"])
+        l, n_cur, keep, cache_len = last["layer"], last["n_cur"], last["keep"], last["cache_len"]
+        x = inputs[(l, K)]
+        src = bufs[l][(K - 1) % 2] if K > 1 else prefix[l]
+        dst = bufs[l][K % 2]
+        idx = torch.stack([torch.sort(torch.randperm(cache_len, device=dev)[:keep])[0] for _ in range(8)])
+        idx = idx.repeat((U + 7) // 8, 1)[:U].reshape(S, H, keep).to(torch.int32).contiguous()
+        ev = events.block(4)
+        reps = 10
+        skv.compact(shape, src[0], src[1], cache_len, idx, keep, x.k_cur, x.v_cur, dst[0], dst[1])
+        hip.hipEventRecord(ev[0], stream_ptr)
+        for _ in range(reps):
+            skv.compact(shape, src[0], src[1], cache_len, idx, keep, x.k_cur, x.v_cur, dst[0], dst[1])
+        hip.hipEventRecord(ev[1], stream_ptr)
+        skv.attend(shape, x.q, dst[0], dst[1], keep + n_cur, outs[K])
+        hip.hipEventRecord(ev[2], stream_ptr)
+        for _ in range(reps):
+            skv.attend(shape, x.q, dst[0], dst[1], keep + n_cur, outs[K])
+        hip.hipEventRecord(ev[3], stream_ptr)
+        torch.cuda.synchronize()
+        c_ms = events.elapsed_ms(ev[0], ev[1]) / reps
+        a_ms = events.elapsed_ms(ev[2], ev[3]) / reps
+        c_bytes = 2.0 * 2.0 * (keep + n_cur) * d * e * U + 4.0 * keep * U
+        a_flops = 4.0 * n_cur * (keep + n_cur) * d * U
+        standalone = {
+            "shape": f"last scale, drafter: cache_len {cache_len}, keep {keep}, n_cur {n_cur}, {U} units",
+            "compact_gather_and_append": {"ms": c_ms, "achieved": c_bytes / (c_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                                          "unit": "GB/s", "frac": c_bytes / (c_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "attend_one_segment_no_append": {"ms": a_ms, "achieved": a_flops / (a_ms * 1e-3) / 1e12,
+                                             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                             "frac": a_flops / (a_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        }
+        log(f"standalone at the last scale: compact {standalone['compact_gather_and_append']['achieved']:.0f} GB/s, "
+            f"attend {standalone['attend_one_segment_no_append']['achieved']:.0f} TFLOP/s")
     events.destroy()
     per_scale_ms = {str(k): v for k, v in per_scale_ms.items()}
 
@@ -447,6 +486,7 @@ def main() -> int:
             "stages": list(stages),
             "ms": ms_stage_pass, "stage_ms": stage_ms, "per_scale_ms": per_scale_ms,
             "per_scale_stage_ms": {str(k): [round(x, 4) for x in v] for k, v in per_scale_stage_ms.items()}},
+        "standalone_kernels": standalone,
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS,
                         "last_scale": gbs(compact_last), "last_scale_frac": gbs(compact_last) / PEAK_HBM_GBS,
