@@ -111,10 +111,10 @@ class HipEvents:
 
 def cpu_baseline(cfg, W, seconds_hint: float = 20.0):
     """The oracle, as it stands, on a bounded sample: every scale of layer 0 for
-    one (sequence, head) unit per host thread.  Extrapolated by unit count."""
+    four (sequence, head) units per host thread.  Extrapolated by unit count."""
     import oracle
     n_thr = oracle.num_threads()
-    units = list(range(min(2 * n_thr, cfg.n_seq * cfg.n_head)))
+    units = list(range(min(4 * n_thr, cfg.n_seq * cfg.n_head)))
     table = W.budget_table(cfg)
     layer = 0
     kp, vp = W.make_prefix(cfg, layer, "cpu", units)
@@ -136,7 +136,7 @@ def cpu_baseline(cfg, W, seconds_hint: float = 20.0):
         "value": est_ms, "unit": "ms per 13-scale image batch (extrapolated by unit count)",
         "cores": n_thr, "kind": "oracle",
         "sample": f"all {cfg.n_scale} scales of layer {layer} for {len(units)} of {cfg.n_seq * cfg.n_head} "
-                  f"(sequence, head) units, two per thread; {dt:.2f} s measured, "
+                  f"(sequence, head) units, four per thread; {dt:.2f} s measured, "
                   f"scaled by {total_units}/{len(units)} units x layers",
         "sample_seconds": dt,
     }

@@ -311,6 +311,33 @@ def test_step_long_cache_and_other_shapes():
         check_output(out, ref["out"], dtype, f"step d={d} L={L}")
 
 
+def test_step_is_reproducible_bit_for_bit_and_stays_inside_its_buffers():
+    # no atomics on floats and a fixed reduction order everywhere: two runs give the same bits;
+    # rows past the new cache length and the spare tail of the output keep their canary
+    S, H, d, n_cur, L, budget = 2, 2, 128, 300, 500, 200
+    dtype = torch.bfloat16
+    _note("step reproducibility")
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = (_rand(60 + i, (S, H, n_cur, d), dtype).to(DEV) for i in range(3))
+    ks, vs = _rand(63, (S, H, L, d), dtype).to(DEV), _rand(64, (S, H, L, d), dtype).to(DEV)
+    ws = torch.zeros(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    runs = []
+    for _ in range(2):
+        kd = torch.full((S, H, budget + n_cur + 9, d), 7.0, dtype=dtype, device=DEV); vd = torch.full_like(kd, 7.0)
+        out = torch.full((S, H, n_cur, d), 7.0, dtype=dtype, device=DEV)
+        idx = torch.full((S, H, budget), -1, dtype=torch.int32, device=DEV)
+        new_len = skv.step(shape, q, kc, vc, list(range(n_cur - 16, n_cur)), ks, vs, L, budget, kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        assert new_len == budget + n_cur
+        assert torch.all(kd[:, :, new_len:] == 7.0) and torch.all(vd[:, :, new_len:] == 7.0)
+        runs.append((kd.clone(), vd.clone(), out.clone(), idx.clone()))
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
+    kd, vd, out, idx = runs[0]
+    assert torch.equal(kd[:, :, budget:budget + n_cur], kc) and torch.equal(vd[:, :, budget:budget + n_cur], vc)
+    assert torch.isfinite(out.float()).all()
+
+
 def test_step_edge_budgets():
     dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 90, 40
     shape = skv.Shape(S, H, d, dtype)
