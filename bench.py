@@ -142,6 +142,61 @@ def cpu_baseline(cfg, W, seconds_hint: float = 20.0):
     }
 
 
+def final_scale_sweep(args, torch, skv, W, cfg) -> int:
+    """--config final_scale: only the 64x64 scale of the 2b_1024 shape, one scalekv_step per
+    budget (5 / 10 / 20 / 100 % of the 6489 cached rows); the 100 % case is uncompressed
+    attention over 10585 keys.  Median of 10 repetitions per budget, HIP events on the launch
+    stream.  One JSON line; `value` is the 10 % case."""
+    dev, dtype = "cuda", torch.bfloat16
+    S, H, d = cfg.n_seq, cfg.n_head, cfg.head_dim
+    U = S * H
+    shape = skv.Shape(S, H, d, dtype)
+    case = W.make_final_scale_case(cfg, dev)
+    n_cur, L = case.q.shape[2], case.k_hist.shape[2]
+    win = W.window_indices(cfg, n_cur)
+    ws = torch.empty(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=dev)
+    out = torch.empty(S, H, n_cur, d, dtype=dtype, device=dev)
+    events = HipEvents(skv.lib())
+    hip = skv.lib()
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    stream_ptr = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for frac, budget in zip(W.FINAL_SCALE_BUDGET_FRACS, W.final_scale_budgets(cfg)):
+        keep = min(budget, L)
+        kd = torch.empty(S, H, keep + n_cur, d, dtype=dtype, device=dev); vd = torch.empty_like(kd)
+        call = skv.PreparedStep(shape, case.q, case.k_cur, case.v_cur, win, case.k_hist, case.v_hist, L, budget,
+                                kd, vd, out, None, ws)
+        for _ in range(max(1, args.warmup)):
+            call(stream_ptr)
+        reps = 10
+        ev = events.block(reps + 1)
+        hip.hipEventRecord(ev[0], stream_ptr)
+        for r in range(reps):
+            call(stream_ptr)
+            hip.hipEventRecord(ev[r + 1], stream_ptr)
+        torch.cuda.synchronize()
+        ms = sorted(events.elapsed_ms(ev[r], ev[r + 1]) for r in range(reps))
+        med = 0.5 * (ms[reps // 2 - 1] + ms[reps // 2])
+        flops = 4.0 * n_cur * (keep + n_cur) * d * U
+        rows.append({"budget_frac": frac, "keep": keep, "kv_len": keep + n_cur, "ms_median": med, "ms_min": ms[0],
+                     "attend_tflop": flops / 1e12, "step_tflops": flops / (med * 1e-3) / 1e12})
+        log(f"budget {frac:.0%}: keep {keep}, {med:.3f} ms per step ({rows[-1]['step_tflops']:.0f} TFLOP/s on the attention flops)")
+        del kd, vd
+    events.destroy()
+    ten = next(r for r in rows if abs(r["budget_frac"] - 0.10) < 1e-9)
+    full = rows[-1]
+    print(json.dumps({
+        "metric": "ScaleKV step ms at the final 64x64 scale, 10 % budget", "value": ten["ms_median"], "unit": "ms",
+        "n_gpus": 1, "steps": 10, "warmup": max(1, args.warmup), "ms_per_step": ten["ms_median"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"final_scale: {S} sequences x {H} heads x d{d}, {n_cur} queries against {L} cached rows "
+                               f"(1 % dominant keys), budgets 5/10/20/100 %, window {cfg.window}"},
+        "sweep": rows,
+        "speedup_10pct_over_uncompressed": full["ms_median"] / ten["ms_median"],
+    }), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,6 +224,8 @@ def main() -> int:
         return 2
     dev = "cuda"
     cfg = W.get_config(args.config)
+    if cfg.name == "final_scale":
+        return final_scale_sweep(args, torch, skv, W, cfg)
     dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     S, H, d, Lyr, K = cfg.n_seq, cfg.n_head, cfg.head_dim, cfg.n_layer, cfg.n_scale
     U = S * H
