@@ -284,6 +284,16 @@ def test_step_chain_8b_shape_heavy_tailed_keys():
     assert stats["exact"] + stats["band"] == 2 * 9 * 3
 
 
+def test_step_chain_2b_1024_full_size_sampled_units():
+    """The bench's own workload at its full size and in its launch configuration (16 x 16 units,
+    all 13 scales up to 4096 queries) for one layer; two units followed by the oracle through
+    every scale."""
+    cfg = W.get_config("2b_1024")
+    stats = _run_chain(cfg, [5], [3, 200], False)
+    _note(f"2b_1024: {stats}")
+    assert stats["exact"] + stats["band"] == cfg.n_scale * 2
+
+
 def test_step_long_cache_and_other_shapes():
     """cache longer than the fused select holds in LDS; head_dim 64 in bf16; fp32 with head_dim 128"""
     for dtype, d, L, n_cur, budget in ((torch.bfloat16, 128, 13000, 40, 700), (torch.bfloat16, 64, 900, 150, 333),
