@@ -348,8 +348,10 @@ def test_step_is_reproducible_bit_for_bit_and_stays_inside_its_buffers():
     assert torch.isfinite(out.float()).all()
 
 
-def test_step_edge_budgets():
-    dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 90, 40
+@pytest.mark.parametrize("n_cur", [40, 160])   # 160: the pipelined attention kernel with its two key segments
+def test_step_edge_budgets(n_cur):
+    dtype, S, H, d, L = torch.bfloat16, 1, 2, 128, 90
+    _note(f"step edge budgets n_cur={n_cur}")
     shape = skv.Shape(S, H, d, dtype)
     q, kc, vc = (_rand(40 + i, (S, H, n_cur, d), dtype) for i in range(3))
     ks, vs = _rand(43, (S, H, L, d), dtype), _rand(44, (S, H, L, d), dtype)
