@@ -348,6 +348,43 @@ def test_step_is_reproducible_bit_for_bit_and_stays_inside_its_buffers():
     assert torch.isfinite(out.float()).all()
 
 
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    # The library neither allocates nor synchronises, so a step can be recorded into a HIP graph;
+    # every replay (with eager work and synchronisations in between) must reproduce the eager bits.
+    S, H, d, n_cur, L, budget = 1, 4, 128, 200, 300, 120
+    dtype = torch.bfloat16
+    _note("step under graph capture")
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = (_rand(70 + i, (S, H, n_cur, d), dtype).to(DEV) for i in range(3))
+    ks, vs = _rand(73, (S, H, L, d), dtype).to(DEV), _rand(74, (S, H, L, d), dtype).to(DEV)
+    ws = torch.zeros(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    win = list(range(n_cur - 16, n_cur))
+    mk = lambda: (torch.zeros(S, H, budget + n_cur, d, dtype=dtype, device=DEV),
+                  torch.zeros(S, H, budget + n_cur, d, dtype=dtype, device=DEV),
+                  torch.zeros(S, H, n_cur, d, dtype=dtype, device=DEV),
+                  torch.zeros(S, H, budget, dtype=torch.int32, device=DEV))
+    kd0, vd0, out0, idx0 = mk()
+    skv.step(shape, q, kc, vc, win, ks, vs, L, budget, kd0, vd0, out0, idx0, ws)     # eager (also first-call set-up)
+    torch.cuda.synchronize()
+    kd, vd, out, idx = mk()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            skv.step(shape, q, kc, vc, win, ks, vs, L, budget, kd, vd, out, idx, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for t in (kd, vd, out):
+            t.fill_(5.0)                    # eager work between replays
+        idx.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(kd, kd0) and torch.equal(vd, vd0), f"replay {rep}"
+        assert torch.equal(out, out0) and torch.equal(idx, idx0), f"replay {rep}"
+
+
 @pytest.mark.parametrize("n_cur", [40, 160])   # 160: the pipelined attention kernel with its two key segments
 def test_step_edge_budgets(n_cur):
     dtype, S, H, d, L = torch.bfloat16, 1, 2, 128, 90
