@@ -348,6 +348,37 @@ def test_step_is_reproducible_bit_for_bit_and_stays_inside_its_buffers():
     assert torch.isfinite(out.float()).all()
 
 
+@pytest.mark.parametrize("n_cur", [48, 200])
+def test_step_with_caches_that_are_views_of_larger_buffers(n_cur):
+    # head stride > capacity * d, for the source and the destination alike
+    S, H, d, L, budget = 2, 3, 128, 260, 100
+    dtype = torch.bfloat16
+    _note(f"step on strided cache views n_cur={n_cur}")
+    shape = skv.Shape(S, H, d, dtype)
+    q, kc, vc = (_rand(80 + i, (S, H, n_cur, d), dtype).to(DEV) for i in range(3))
+    big_k, big_v = _rand(83, (S, H, L + 77, d), dtype).to(DEV), _rand(84, (S, H, L + 77, d), dtype).to(DEV)
+    ks, vs = big_k[:, :, :L + 5], big_v[:, :, :L + 5]
+    cap = budget + n_cur
+    kd_big = torch.full((S, H, cap + 40, d), 3.0, dtype=dtype, device=DEV); vd_big = torch.full_like(kd_big, 3.0)
+    kd, vd = kd_big[:, :, :cap], vd_big[:, :, :cap]
+    out = torch.zeros(S, H, n_cur, d, dtype=dtype, device=DEV)
+    idx = torch.zeros(S, H, budget, dtype=torch.int32, device=DEV)
+    ws = torch.zeros(skv.workspace_bytes(shape, L, n_cur), dtype=torch.uint8, device=DEV)
+    win = list(range(n_cur - 16, n_cur))
+    new_len = skv.step(shape, q, kc, vc, win, ks, vs, L, budget, kd, vd, out, idx, ws)
+    torch.cuda.synchronize()
+    assert new_len == cap
+    assert torch.all(kd_big[:, :, cap:] == 3.0) and torch.all(vd_big[:, :, cap:] == 3.0)
+    g_idx = idx.cpu().numpy().reshape(S * H, budget)
+    own = oracle.step(units(q), units(kc), units(vc), win, units(ks)[:, :L], units(vs)[:, :L], budget)
+    for u in range(S * H):
+        check_indices(g_idx[u], own["scores"][u], budget, own["idx"][u])
+    ref = oracle.step(units(q), units(kc), units(vc), win, units(ks)[:, :L], units(vs)[:, :L], budget, force_idx=g_idx)
+    assert np.array_equal(units(kd.contiguous()).double().numpy(), ref["k_dst"])
+    assert np.array_equal(units(vd.contiguous()).double().numpy(), ref["v_dst"])
+    check_output(out, ref["out"], dtype, "strided step")
+
+
 def test_step_can_be_captured_in_a_graph_and_replayed():
     # The library neither allocates nor synchronises, so a step can be recorded into a HIP graph;
     # every replay (with eager work and synchronisations in between) must reproduce the eager bits.
