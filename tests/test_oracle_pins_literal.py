@@ -38,7 +38,8 @@ def test_centroids_small_maps_use_every_token():
     assert len(oracle.window_centroids(2, 6, 4, 4)) == 8
 
 
-@pytest.mark.parametrize("h,w,ph,pw", [(6, 6, 4, 4), (6, 10, 4, 4), (20, 20, 4, 4), (7, 5, 2, 3), (48, 48, 4, 4)])
+@pytest.mark.parametrize("h,w,ph,pw", [(6, 6, 4, 4), (6, 10, 4, 4), (10, 6, 4, 4), (10, 10, 4, 4), (20, 20, 4, 4),
+                                      (7, 5, 2, 3), (11, 13, 3, 5), (48, 48, 4, 4)])
 def test_centroids_minimise_distance_to_the_patch_centre(h, w, ph, pw):
     got = oracle.window_centroids(h, w, ph, pw)
     assert np.all(np.diff(got) > 0)
