@@ -45,14 +45,14 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # 2.0: what the same counter reads for a plain copy of known size) plus --pmc WRITE_SIZE (KiB,
 # scale 1.0), three launches each, inside scalekv_step.  The commands and the full per-kernel table are in profiles/step_hbm_traffic.md.
 ATTEND_PIPE_TRAFFIC = {
-    (144, 46): 71.2e6, (144, 9): 65.8e6,
-    (256, 82): 147.1e6, (256, 16): 139.7e6,
-    (400, 146): 215.5e6, (400, 29): 202.1e6,
-    (576, 246): 319.0e6, (576, 49): 295.4e6,
-    (1024, 390): 552.0e6, (1024, 78): 520.1e6,
-    (1600, 646): 909.0e6, (1600, 129): 822.0e6,
-    (2304, 1046): 1405.4e6, (2304, 209): 1263.1e6,
-    (4096, 1622): 2150.0e6, (4096, 324): 2048.0e6,
+    (144, 46): 63.2e6, (144, 9): 58.4e6,
+    (256, 82): 136.6e6, (256, 16): 131.0e6,
+    (400, 146): 198.2e6, (400, 29): 185.3e6,
+    (576, 246): 295.8e6, (576, 49): 272.4e6,
+    (1024, 390): 513.1e6, (1024, 78): 480.9e6,
+    (1600, 646): 850.2e6, (1600, 129): 767.9e6,
+    (2304, 1046): 1326.3e6, (2304, 209): 1177.2e6,
+    (4096, 1622): 1999.6e6, (4096, 324): 1897.6e6,
 }
 
 
