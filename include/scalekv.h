@@ -109,7 +109,7 @@ scalekv_status scalekv_select(const scalekv_shape* shape, const float* scores, i
  * n_cur == 0.  Copies are bit-exact.  The byte spans of the two
  * source caches and the two destination caches (first to last addressable
  * element of each) must be pairwise disjoint, except that k_src may alias
- * v_src.  Requires keep + n_cur <= dst capacity and idx entries in
+ * v_src, and k_cur / v_cur must not overlap a destination cache.  Requires keep + n_cur <= dst capacity and idx entries in
  * [0, cache_len) (entries are not checked on the device). */
 scalekv_status scalekv_compact(const scalekv_shape* shape, const scalekv_kv* k_src,
                                const scalekv_kv* v_src, int32_t cache_len, const int32_t* idx,
@@ -132,7 +132,9 @@ scalekv_status scalekv_attend(const scalekv_shape* shape, const void* q, int32_t
  * (device, [S,H,keep]) is not NULL, the selected indices.  *new_len_out (host,
  * may be NULL) = keep + n_cur.  budget >= cache_len keeps everything and skips
  * scoring (the result is exact attention over cache and current map);
- * budget == 0 attends over the current map only.  n_cur >= 1. */
+ * budget == 0 attends over the current map only.  n_cur >= 1.  q, k_cur, v_cur and out
+ * must not overlap k_dst / v_dst (the destination is written while they are in use);
+ * such an overlap -> INVALID_ARG, as for overlapping source and destination caches. */
 scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const void* k_cur,
                             const void* v_cur, int32_t n_cur, const int32_t* win_idx,
                             int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,

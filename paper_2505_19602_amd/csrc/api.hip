@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <algorithm>
 #include <cmath>
 #include <vector>
@@ -106,6 +107,16 @@ bool overlaps(const scalekv_shape* s, const scalekv_kv* a, const scalekv_kv* b) 
   kv_span(s, a, &al, &ah);
   kv_span(s, b, &bl, &bh);
   return al < bh && bl < ah;
+}
+
+// does the dense tensor [S, H, rows, d] at p overlap the byte span of a cache?
+bool dense_overlaps(const scalekv_shape* s, const void* p, long long rows, const scalekv_kv* kv) {
+  if (!p || rows <= 0) return false;
+  uintptr_t kl, kh;
+  kv_span(s, kv, &kl, &kh);
+  const uintptr_t pl = reinterpret_cast<uintptr_t>(p);
+  const uintptr_t ph = pl + (uintptr_t)((long long)s->n_seq * s->n_head * rows * s->head_dim * elem_bytes(s));
+  return pl < kh && kl < ph;
 }
 
 KvView view(const scalekv_kv* kv) { return KvView{kv->ptr, kv->seq_stride, kv->head_stride}; }
@@ -274,6 +285,9 @@ scalekv_status scalekv_compact(const scalekv_shape* shape, const scalekv_kv* k_s
       overlaps(shape, v_src, k_dst) || overlaps(shape, v_src, v_dst) ||
       overlaps(shape, k_dst, v_dst))
     return fail(SCALEKV_ERR_INVALID_ARG, "source and destination caches overlap");
+  if (dense_overlaps(shape, k_cur, n_cur, k_dst) || dense_overlaps(shape, k_cur, n_cur, v_dst) ||
+      dense_overlaps(shape, v_cur, n_cur, k_dst) || dense_overlaps(shape, v_cur, n_cur, v_dst))
+    return fail(SCALEKV_ERR_INVALID_ARG, "k_cur / v_cur overlap a destination cache");
   SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
                              view(k_src), view(v_src), idx, keep, k_cur, v_cur, n_cur, view(k_dst),
                              view(v_dst), static_cast<hipStream_t>(stream)),
@@ -338,6 +352,11 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
       overlaps(shape, v_src, k_dst) || overlaps(shape, v_src, v_dst) ||
       overlaps(shape, k_dst, v_dst))
     return fail(SCALEKV_ERR_INVALID_ARG, "source and destination caches overlap");
+  // the destination caches are written while q, k_cur, v_cur are still being read and out is written
+  for (const scalekv_kv* c : {k_dst, v_dst})
+    if (dense_overlaps(shape, q, n_cur, c) || dense_overlaps(shape, k_cur, n_cur, c) ||
+        dense_overlaps(shape, v_cur, n_cur, c) || dense_overlaps(shape, out, n_cur, c))
+      return fail(SCALEKV_ERR_INVALID_ARG, "q, k_cur, v_cur or out overlaps a destination cache");
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   void** ev = g_stage_events;
@@ -494,6 +513,10 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
   SCALEKV_TRY(check_kv(shape, v_cache, len, "v_cache"));
   if (overlaps(shape, k_cache, v_cache))
     return fail(SCALEKV_ERR_INVALID_ARG, "k_cache and v_cache overlap");
+  for (const scalekv_kv* c : {k_cache, v_cache})
+    if (dense_overlaps(shape, q, n_cur, c) || dense_overlaps(shape, k_cur, n_cur, c) ||
+        dense_overlaps(shape, v_cur, n_cur, c) || dense_overlaps(shape, out, n_cur, c))
+      return fail(SCALEKV_ERR_INVALID_ARG, "q, k_cur, v_cur or out overlaps a cache that is written");
   if (moves) {
     SCALEKV_TRY(check_kv(shape, k_next, keep, "k_next"));
     SCALEKV_TRY(check_kv(shape, v_next, keep, "v_next"));

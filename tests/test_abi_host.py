@@ -226,3 +226,24 @@ def test_step_append_first_argument_errors(L):
     assert step(vc=k) == 1 and "overlap" in _err(L)
     assert step(k_next=k) == 1 and "overlap" in _err(L)
     assert step(w=(ctypes.c_int32 * 4)(0, 1, 2, 2)) == 1 and "repeats" in _err(L)
+
+
+def test_step_and_compact_reject_inputs_that_overlap_the_destination(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    big = ctypes.c_size_t(1 << 30)
+    src_k, src_v = _kv(0x100000), _kv(0x200000)
+    dst_k, dst_v = _kv(0x300000), _kv(0x400000)            # 64 rows x 128 x 2 heads x 2 B = 32 KiB each
+    win = (ctypes.c_int32 * 1)(0)
+    new_len = ctypes.c_int32(-1)
+    def step(q, kc, vc, out):
+        return L.scalekv_step(ctypes.byref(s), p(q), p(kc), p(vc), 8, win, 1, ctypes.byref(src_k), ctypes.byref(src_v),
+                              20, 5, ctypes.byref(dst_k), ctypes.byref(dst_v), ctypes.byref(new_len), p(out), None,
+                              p(0x800000), big, None)
+    assert step(0x300000 + 4096, 0x600000, 0x700000, 0x900000) == 1 and "overlaps a destination" in _err(L)
+    assert step(0x500000, 0x400000, 0x700000, 0x900000) == 1
+    assert step(0x500000, 0x600000, 0x300000 - 256, 0x900000) == 1      # its last bytes reach into k_dst
+    assert step(0x500000, 0x600000, 0x700000, 0x400000 + 32 * 1024 - 16) == 1
+    assert L.scalekv_compact(ctypes.byref(s), ctypes.byref(src_k), ctypes.byref(src_v), 20, None, 5, p(0x300000), p(0x700000),
+                             8, ctypes.byref(dst_k), ctypes.byref(dst_v), None) == 1
+    assert "overlap a destination" in _err(L)
