@@ -16,14 +16,16 @@
 // so registers r = 8m..8m+7 of an S^T block are keys 16m + 8h + (0..7) of the
 // block: already the B operand of the second product.
 //
-// Occupancy.  On this chip a wave's own VALU work does not run under its own
-// MFMAs (measured: independent VALU instructions placed behind an MFMA add their
-// full issue time), so the softmax can only hide behind the matrix pipe if a second
-// wave shares the SIMD.  The kernel is therefore written for two workgroups of 4
-// waves per CU: every wave owns 32 query rows, stays under 256 registers, and runs
-// plain in-order code (S, softmax, PV per block of 32 keys); the two workgroups
-// drift apart and fill each other's gaps.  LDS operand traffic is 16 KB per wave
-// and block, half of what the LDS delivers at full MFMA rate.
+// Occupancy.  Vector instructions that follow a run of a wave's own MFMAs wait for the
+// run (the wave issues in order and stalls at each MFMA until the pipe takes it), so
+// the softmax of a block hides behind the matrix pipe only if a second wave shares
+// the SIMD, or if it is cut up and spread between the MFMAs of another product.  The
+// second form was built as well (blocks skewed by one, PV(b-1) interleaved with the
+// softmax of block b) and measured 2-3 % slower than this one.  The kernel is written
+// for two workgroups of 4 waves per CU: every wave owns 32 query rows, stays under
+// 256 registers, and runs plain in-order code (S, softmax, PV per block of 32 keys);
+// the two workgroups drift apart and fill each other's gaps.  LDS operand traffic is
+// 16 KB per wave and block, half of what the LDS delivers at full MFMA rate.
 //
 // Data movement.  K and V tiles (64 keys x 256 B) go from HBM/L2 straight into LDS
 // (global_load_lds, 16 B per lane, no registers), row-major, with the 16-byte
