@@ -41,8 +41,7 @@ __global__ __launch_bounds__(kThreads) void asi_terms_kernel(ScoreWorkspace ws, 
                                                              float* __restrict__ terms, int n_samp,
                                                              int row0) {
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t sel[2];
+  __shared__ __attribute__((aligned(16))) uint32_t hist[kRadixHistWords];
   __shared__ float red[kWaves];
   __shared__ float shift_s;
 
@@ -72,7 +71,7 @@ __global__ __launch_bounds__(kThreads) void asi_terms_kernel(ScoreWorkspace ws, 
       else return order_key(logit(i));
     };
     uint32_t T = 0, need_eq = 0;
-    if (kk < hist_len) radix_kth_largest<kThreads>(key_at, hist_len, (uint32_t)kk, hist, sel, T, need_eq);
+    if (kk < hist_len) radix_kth_largest<kThreads>(key_at, hist_len, (uint32_t)kk, hist, T, need_eq);
     part = 0.f;
     for (int i = tid; i < hist_len; i += kThreads) {
       const uint32_t key = key_at(i);

@@ -393,14 +393,10 @@ template <int D, int QB>
 hipError_t launch_mfma(dim3 grid, hipStream_t stream, const uint16_t* q, int n_q, const uint16_t* k,
                        KvView kv, const uint16_t* v, KvView vv, int kv_len, int n_head,
                        float scale_log2e, uint16_t* out) {
-  static bool configured = false;  // LDS above 64 KB per workgroup has to be asked for once
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_mfma_kernel<D, QB>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       AttendLds<D>::kBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<uint64_t> configured{0};  // LDS above 64 KB per workgroup has to be asked for
+  const hipError_t e = allow_dynamic_lds((const void*)attend_mfma_kernel<D, QB>,
+                                         AttendLds<D>::kBytes, configured);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attend_mfma_kernel<D, QB>), grid, dim3(256), AttendLds<D>::kBytes, stream, q,
                      n_q, k, kv.seq_stride, kv.head_stride, v, vv.seq_stride, vv.head_stride,
                      kv_len, n_head, scale_log2e, out);

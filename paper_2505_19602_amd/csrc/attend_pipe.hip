@@ -467,13 +467,9 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
 hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
                               int len1, const void* k2, const void* v2, int len2, bool append,
                               float sm_scale, void* out, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_pipe_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<uint64_t> configured{0};
+  const hipError_t e = allow_dynamic_lds((const void*)attend_pipe_kernel, kLdsBytes, configured);
+  if (e != hipSuccess) return e;
   const float scale_log2e = sm_scale * 1.4426950408889634f;
   const int n_qtile = (n_q + BM - 1) / BM;
   const int n_wg = n_qtile * n_unit;

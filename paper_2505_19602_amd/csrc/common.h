@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace scalekv {
 
 constexpr int kMaxWindow = 16;     // window rows held per unit by the score kernels
@@ -36,6 +38,21 @@ struct SelectExtras {
 };
 
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Raises a kernel's dynamic-LDS limit, once per device: the attribute belongs to the current
+// device's copy of the code, so a second GPU needs its own call.  `done` holds one bit per
+// device (devices 64 and up are simply set every time); any number of host threads may race
+// here, the call is idempotent.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // ---- launchers (each enqueues on `stream` and returns hipGetLastError()) ----
 

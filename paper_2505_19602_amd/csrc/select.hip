@@ -46,8 +46,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   constexpr int kPerThread = IN_LDS ? kLdsKeys / kThreads : 1;
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
   __shared__ float row_shift[kMaxWindow];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t sel[2];
+  __shared__ __attribute__((aligned(16))) uint32_t hist[kRadixHistWords];
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
 
   const int unit = blockIdx.x;
@@ -98,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
 
   // ---- radix select: T = key of the keep-th largest ----
   uint32_t T, need_eq;  // need_eq: how many keys equal to T are taken (>= 1)
-  radix_kth_largest<kThreads>(key_at, cache_len, (uint32_t)keep, hist, sel, T, need_eq);
+  radix_kth_largest<kThreads>(key_at, cache_len, (uint32_t)keep, hist, T, need_eq);
 
   // ---- stable emission ----
   const int per = (cache_len + kThreads - 1) / kThreads;
@@ -111,12 +110,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   }
   // exclusive block scan of (n_gt, n_eq)
   const int lane = tid & 63, wave = tid >> 6;
-  uint32_t sg = n_gt, se = n_eq;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t og = __shfl_up(sg, off), oe = __shfl_up(se, off);
-    if (lane >= off) { sg += og; se += oe; }
-  }
+  const uint32_t sg = wave_prefix_sum(n_gt, lane), se = wave_prefix_sum(n_eq, lane);
   if (lane == 63) { wave_gt[wave] = sg; wave_eq[wave] = se; }
   __syncthreads();
   uint32_t base_g = 0, base_e = 0;
