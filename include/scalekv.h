@@ -244,6 +244,20 @@ scalekv_status scalekv_allocate_budgets(int32_t n_layer, int32_t n_scale, const 
                                         int64_t b_uniform, int64_t b_r0, int64_t delta,
                                         int64_t b_min, int32_t* b_r, int32_t* b_d, int64_t* slack);
 
+/* Eq. 3 and Eq. 4 in one call: from the measured ASI of every (layer, scale) pair to the
+ * budget each scalekv_step call of that pair is given (Sec. 3.2: drafters get the large
+ * budget, refiners the small, shrinking one).  Host only.  asi, n_drafter, eps as in
+ * scalekv_drafter_set (n_drafter >= 1 here, at most n_layer*n_scale); b_uniform, b_r0, delta,
+ * b_min as in scalekv_allocate_budgets, whose per-scale drafter counts are those of the
+ * drafter set just found.  table (host, [n_layer][n_scale]) receives *b_d for a drafter pair
+ * and b_r[k-1] for a refiner pair; is_drafter (host, same shape), b_r (host, [n_scale]),
+ * b_d and slack (host) may each be NULL.  Errors are those of the two calls. */
+scalekv_status scalekv_policy_table(const double* asi, int32_t n_layer, int32_t n_scale,
+                                    int32_t n_drafter, double eps, int64_t b_uniform,
+                                    int64_t b_r0, int64_t delta, int64_t b_min, int32_t* table,
+                                    int32_t* is_drafter, int32_t* b_r, int32_t* b_d,
+                                    int64_t* slack);
+
 /* ---- Comparison policies of Sec. 4.1 ("Compression Baselines"), as index / budget
  * generators for the same compact and attend calls; each is built from the one line the
  * paper gives it. ---- */

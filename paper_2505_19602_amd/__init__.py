@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     drafter_set,
     allocate_budgets,
     pyramid_budgets,
+    policy_table,
     select_positional,
     MAX_WINDOW,
     MAX_ASI_SAMPLES,

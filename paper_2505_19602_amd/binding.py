@@ -26,7 +26,7 @@ _STATUS_SYMBOLS = (
     "scalekv_attend", "scalekv_step", "scalekv_step_stage_events",
     "scalekv_window_centroids", "scalekv_select_window", "scalekv_step_append_first",
     "scalekv_asi", "scalekv_drafter_set", "scalekv_allocate_budgets", "scalekv_select_positional",
-    "scalekv_pyramid_budgets",
+    "scalekv_pyramid_budgets", "scalekv_policy_table",
 )
 EXPORTED_SYMBOLS = _STATUS_SYMBOLS + ("scalekv_last_error", "scalekv_version")
 
@@ -429,6 +429,24 @@ def allocate_budgets(n_layer: int, n_drafter: Sequence[int], b_uniform: int, b_r
                                           ctypes.c_int64(b_r0), ctypes.c_int64(delta), ctypes.c_int64(b_min),
                                           b_r, ctypes.byref(b_d), ctypes.byref(slack)))
     return [int(b_r[k]) for k in range(K)], int(b_d.value), int(slack.value)
+
+
+def policy_table(asi_lk, n_drafter: int, b_uniform: int, b_r0: int, delta: int, b_min: int = 0,
+                 eps: float = 1e-8):
+    """scalekv_policy_table: ASI [L][K] (host) -> (table [L][K] of per-step budgets,
+    is_drafter [L][K], b_r [K], b_d, slack)."""
+    L, K = len(asi_lk), len(asi_lk[0])
+    flat = (ctypes.c_double * (L * K))(*[float(x) for row in asi_lk for x in row])
+    table = (ctypes.c_int32 * (L * K))()
+    mask = (ctypes.c_int32 * (L * K))()
+    b_r = (ctypes.c_int32 * K)()
+    b_d, slack = ctypes.c_int32(-1), ctypes.c_int64(-1)
+    _check(lib().scalekv_policy_table(flat, int(L), int(K), int(n_drafter), ctypes.c_double(eps),
+                                      ctypes.c_int64(b_uniform), ctypes.c_int64(b_r0), ctypes.c_int64(delta),
+                                      ctypes.c_int64(b_min), table, mask, b_r, ctypes.byref(b_d),
+                                      ctypes.byref(slack)))
+    grid = lambda a: [[int(a[l * K + k]) for k in range(K)] for l in range(L)]
+    return grid(table), grid(mask), [int(b_r[k]) for k in range(K)], int(b_d.value), int(slack.value)
 
 
 def pyramid_budgets(n_layer: int, b_uniform: int, b_last: int) -> list:

@@ -715,6 +715,37 @@ scalekv_status scalekv_allocate_budgets(int32_t n_layer, int32_t n_scale, const 
   return SCALEKV_OK;
 }
 
+scalekv_status scalekv_policy_table(const double* asi, int32_t n_layer, int32_t n_scale,
+                                    int32_t n_drafter, double eps, int64_t b_uniform,
+                                    int64_t b_r0, int64_t delta, int64_t b_min, int32_t* table,
+                                    int32_t* is_drafter, int32_t* b_r, int32_t* b_d,
+                                    int64_t* slack) {
+  if (!table) return fail(SCALEKV_ERR_INVALID_ARG, "table is NULL");
+  if (n_drafter < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_drafter must be >= 1 (got %d)", n_drafter);
+  if (n_layer < 1 || n_scale < 1)
+    return fail(SCALEKV_ERR_INVALID_ARG, "n_layer and n_scale must be positive (got %d, %d)",
+                n_layer, n_scale);
+  if ((long long)n_layer * n_scale > 0x7fffffffLL)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "n_layer * n_scale is too large");
+  const size_t total = (size_t)n_layer * n_scale;
+  std::vector<int32_t> role(total), per_scale((size_t)n_scale, 0), refiner((size_t)n_scale);
+  SCALEKV_TRY(scalekv_drafter_set(asi, n_layer, n_scale, n_drafter, eps, nullptr, role.data()));
+  for (int l = 0; l < n_layer; ++l)
+    for (int k = 0; k < n_scale; ++k) per_scale[k] += role[(size_t)l * n_scale + k];
+  int32_t drafter = 0;
+  int64_t rest = 0;
+  SCALEKV_TRY(scalekv_allocate_budgets(n_layer, n_scale, per_scale.data(), b_uniform, b_r0, delta,
+                                       b_min, refiner.data(), &drafter, &rest));
+  for (int l = 0; l < n_layer; ++l)
+    for (int k = 0; k < n_scale; ++k)
+      table[(size_t)l * n_scale + k] = role[(size_t)l * n_scale + k] ? drafter : refiner[k];
+  if (is_drafter) std::memcpy(is_drafter, role.data(), total * sizeof(int32_t));
+  if (b_r) std::memcpy(b_r, refiner.data(), (size_t)n_scale * sizeof(int32_t));
+  if (b_d) *b_d = drafter;
+  if (slack) *slack = rest;
+  return SCALEKV_OK;
+}
+
 scalekv_status scalekv_pyramid_budgets(int32_t n_layer, int64_t b_uniform, int64_t b_last,
                                        int32_t* b) {
   if (n_layer < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_layer must be positive (got %d)", n_layer);

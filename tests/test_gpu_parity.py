@@ -214,14 +214,17 @@ def test_attend_closed_forms_on_gpu():
 
 # ------------------------------------------------------------------- step --
 
-def _run_chain(cfg, layers, unit_ids, check_all_units, last_scale=None):
+def _run_chain(cfg, layers, unit_ids, check_all_units, last_scale=None, table=None):
     """Run all scales of `cfg` for the given layers on the GPU through
-    scalekv_step and follow each (layer, unit) with the oracle."""
+    scalekv_step and follow each (layer, unit) with the oracle.  `table`: budgets per
+    [layer][scale - 1] in place of the config's own."""
     dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     S, H, d = cfg.n_seq, cfg.n_head, cfg.head_dim
     shape = skv.Shape(S, H, d, dtype)
-    cap = W.dst_capacity(cfg)
-    table = W.budget_table(cfg)
+    if table is None:
+        table = W.budget_table(cfg)
+    cap = max(min(table[l][k - 1], W.c_full(cfg, k)) + cfg.n_tokens(k)
+              for l in range(cfg.n_layer) for k in range(1, cfg.n_scale + 1))
     ws = torch.empty(skv.workspace_bytes(shape, cap, max(cfg.n_tokens(k) for k in range(1, cfg.n_scale + 1))),
                      dtype=torch.uint8, device=DEV)
     stats = dict(exact=0, band=0, max_err=0.0)

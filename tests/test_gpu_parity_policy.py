@@ -1,6 +1,7 @@
 """GPU parity for the offline policy and the comparison policies: scalekv_asi (Eq. 2)
-and scalekv_select_positional (Sec. 4.1) through the C ABI against the oracle, and the
-positional indices driving the same compact / attend kernels as the method's own."""
+and scalekv_select_positional (Sec. 4.1) through the C ABI against the oracle, the
+positional indices driving the same compact / attend kernels as the method's own, and the
+whole policy in one chain: measured ASI -> drafter set and budgets (Eq. 3, 4) -> steps."""
 import numpy as np
 import pytest
 import torch
@@ -124,3 +125,50 @@ def test_positional_indices_drive_the_same_compact_and_attend():
     assert np.array_equal(units(kd).double().numpy(), k_ref)
     ref = oracle.attend(units(q), k_ref, v_ref)
     check_output(out, ref, dtype, "positional policy attend")
+
+
+def test_calibrated_policy_chain_from_asi_to_steps():
+    """Sec. 3.2 end to end on a small workload: the ASI of every (layer, scale) pair is measured
+    on the uncompressed cache (GPU against oracle), Eq. 3 and Eq. 4 turn the GPU's values into
+    the budget table (library against the oracle's three routines on the same numbers), and
+    the step sequence run with that table is followed by the oracle on every unit."""
+    from test_gpu_parity import _run_chain
+    cfg = W.get_config("calib_small")
+    n_layer, n_scale, S, H, d = cfg.n_layer, cfg.n_scale, cfg.n_seq, cfg.n_head, cfg.head_dim
+    shape = skv.Shape(S, H, d, torch.bfloat16)
+    TOP_K, N_SAMP = 8, 16
+    N_D, B_UNI, B_R0, DELTA, B_MIN = 2 * n_scale, 60, 44, 5, 4
+    asi_gpu, asi_ref = np.zeros((n_layer, n_scale)), np.zeros((n_layer, n_scale))
+    for l in range(n_layer):
+        for k in range(1, n_scale + 1):
+            _note(f"asi cfg={cfg.name} layer={l} scale={k}")
+            c = W.make_asi_case(cfg, l, k, DEV, N_SAMP)
+            n_s = c.q_samp.shape[2]
+            terms = torch.empty(S, H, n_s, 2, dtype=torch.float32, device=DEV)
+            out3 = torch.empty(3, dtype=torch.float32, device=DEV)
+            ws = torch.empty(skv.workspace_bytes(shape, c.hist_len + c.cur_len, n_s), dtype=torch.uint8, device=DEV)
+            skv.asi(shape, c.q_samp, c.k_all, c.hist_len, c.cur_len, TOP_K, terms, out3, ws)
+            torch.cuda.synchronize()
+            asi_gpu[l, k - 1] = float(out3[2])
+            cur, top = oracle.asi_terms(units(c.q_samp), units(c.k_all), c.hist_len, TOP_K)
+            asi_ref[l, k - 1] = oracle.asi(cur, top)
+    assert np.allclose(asi_gpu, asi_ref, rtol=2 * ASI_RTOL, atol=ASI_ATOL), np.abs(asi_gpu - asi_ref).max()
+
+    table, mask, b_r, b_d, slack = skv.policy_table(asi_gpu.tolist(), N_D, B_UNI, B_R0, DELTA, B_MIN)
+    # the host routine against the oracle's Eq. 3 / Eq. 4 on the very same ASI values
+    z = oracle.zscores(asi_gpu)
+    want_mask = oracle.drafters(z, N_D)
+    want_b_r, want_b_d, want_slack = oracle.budgets(n_layer, want_mask.sum(axis=0), B_UNI, B_R0, DELTA, B_MIN)
+    assert np.array_equal(np.array(mask), want_mask)
+    assert (b_r, b_d, slack) == (want_b_r.tolist(), want_b_d, want_slack)
+    assert np.array_equal(np.array(table), np.where(want_mask == 1, want_b_d, want_b_r[None, :]))
+    # where the cut between the N_D-th and the next Z-score is wider than the ASI tolerance can
+    # move it, the oracle's own ASI picks the same drafters
+    z_ref = np.sort(oracle.zscores(asi_ref).ravel())
+    if z_ref[N_D] - z_ref[N_D - 1] > 0.05:
+        assert np.array_equal(oracle.drafters(oracle.zscores(asi_ref), N_D), want_mask)
+    _note(f"calibrated table: b_d={b_d} b_r={b_r} drafters per scale={want_mask.sum(axis=0).tolist()}")
+
+    stats = _run_chain(cfg, range(n_layer), None, True, table=table)
+    _note(f"calibrated chain: {stats}")
+    assert stats["exact"] + stats["band"] == n_layer * n_scale * S * H

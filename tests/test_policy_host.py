@@ -96,6 +96,66 @@ def test_allocate_budgets_argument_errors(L):
     assert call(4, 2, nd, i64(10), i64(5), i64(1), i64(0), br, ctypes.byref(bd), None) == 0   # slack optional
 
 
+def _oracle_table(asi, n_d, bu, br0, delta, b_min, eps=1e-8):
+    """Eq. 3 then Eq. 4 through the oracle, and the budget of every (layer, scale) pair."""
+    mask = oracle.drafters(oracle.zscores(asi, eps=eps), n_d)
+    sol = oracle.budgets(asi.shape[0], mask.sum(axis=0), bu, br0, delta, b_min)
+    if sol is None:
+        return None
+    b_r, b_d, slack = sol
+    return np.where(mask == 1, b_d, b_r[None, :]), mask, b_r, b_d, slack
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_policy_table_matches_the_oracle(L, seed):
+    rng = np.random.default_rng(300 + seed)
+    nl, nk = int(rng.integers(2, 41)), int(rng.integers(1, 14))
+    asi = rng.uniform(0.0, 1.0, size=(nl, nk)) * rng.uniform(0.01, 10, size=(1, nk))
+    n_d = int(rng.integers(1, nl * nk + 1))
+    bu, br0 = int(rng.integers(50, 2000)), int(rng.integers(0, 300))
+    delta, b_min = int(rng.integers(0, 40)), int(rng.integers(0, 5))
+    want = _oracle_table(asi, n_d, bu, br0, delta, b_min)
+    if want is None:
+        with pytest.raises(skv.ScaleKVError):
+            skv.policy_table(asi.tolist(), n_d, bu, br0, delta, b_min)
+        return
+    table, mask, b_r, b_d, slack = skv.policy_table(asi.tolist(), n_d, bu, br0, delta, b_min)
+    assert np.array_equal(np.array(table), want[0]) and np.array_equal(np.array(mask), want[1])
+    assert b_r == want[2].tolist() and (b_d, slack) == (want[3], want[4])
+    # Eq. 4 itself: the budgets handed out add up to the uniform total, short by the slack
+    assert int(np.array(table).sum()) + slack == bu * nl * nk
+
+
+def test_policy_table_with_the_papers_numbers(L):
+    """32 layers, 13 scales, 104 drafter pairs, B_uniform 650, B_r(0) 600, delta 70 (Sec. 4.1 /
+    Appendix): whatever the ASI values, refiners follow the clamped line and Eq. 4 balances."""
+    rng = np.random.default_rng(7)
+    asi = rng.uniform(0.0, 1.0, size=(32, 13))
+    table, mask, b_r, b_d, slack = skv.policy_table(asi.tolist(), 104, 650, 600, 70)
+    assert b_r == [530, 460, 390, 320, 250, 180, 110, 40, 0, 0, 0, 0, 0]
+    assert int(np.array(mask).sum()) == 104
+    assert int(np.array(table).sum()) + slack == 650 * 32 * 13 and 0 <= slack < 104
+    want = _oracle_table(asi, 104, 650, 600, 70, 0)
+    assert np.array_equal(np.array(table), want[0])
+
+
+def test_policy_table_argument_errors(L):
+    d = ctypes.c_double * 4
+    t = (ctypes.c_int32 * 4)()
+    i64 = ctypes.c_int64
+    args = lambda asi, nl, nk, nd, tab: (asi, nl, nk, nd, ctypes.c_double(1e-8), i64(100), i64(50), i64(10), i64(0),
+                                        tab, None, None, None, None)
+    assert L.scalekv_policy_table(*args(d(1, 2, 3, 4), 2, 2, 1, t)) == 0
+    assert L.scalekv_policy_table(*args(d(1, 2, 3, 4), 2, 2, 1, None)) == 1
+    assert L.scalekv_policy_table(*args(d(1, 2, 3, 4), 2, 2, 0, t)) == 1      # nothing could take the pool
+    assert L.scalekv_policy_table(*args(None, 2, 2, 1, t)) == 1
+    assert L.scalekv_policy_table(*args(d(1, 2, 3, 4), 0, 2, 1, t)) == 1
+    # refiners alone above the total
+    assert L.scalekv_policy_table(d(1, 2, 3, 4), 2, 2, 1, ctypes.c_double(1e-8), i64(10), i64(500), i64(0), i64(0),
+                                  t, None, None, None, None) == 1
+    assert "exceed" in _err(L)
+
+
 @pytest.mark.parametrize("nl,bu,bl", [(1, 7, 7), (2, 9, 4), (7, 100, 30), (8, 100, 30), (32, 650, 100), (40, 649, 0), (5, 10, 10)])
 def test_pyramid_budgets_match_the_oracle(L, nl, bu, bl):
     assert skv.pyramid_budgets(nl, bu, bl) == oracle.pyramid(nl, bu, bl).tolist()

@@ -30,4 +30,8 @@ from .generator import (  # noqa: F401
     make_prefix,
     make_step_inputs,
     make_final_scale_case,
+    AsiCase,
+    asi_sample_rows,
+    assemble_asi_case,
+    make_asi_case,
 )

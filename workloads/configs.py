@@ -100,6 +100,12 @@ CONFIGS = {
     "final_scale": WorkloadConfig(
         name="final_scale", dtype="bf16", n_seq=16, n_layer=1, n_head=16, head_dim=128, prefix=64,
         sides=_SIDES_1024, window=16, recipe="dominant", n_drafter=0),
+    # small bf16 case for the calibrated-policy chain (ASI -> drafter set -> budgets -> steps):
+    # few enough units that the fp64 oracle can follow every one of them.
+    "calib_small": WorkloadConfig(
+        name="calib_small", dtype="bf16", n_seq=2, n_layer=6, n_head=4, head_dim=128, prefix=32,
+        sides=(1, 2, 4, 6, 8, 12, 16), window=16, recipe="lowrank8", n_drafter=2,
+        drafter_frac=0.25, refiner_frac=0.05),
 }
 
 FINAL_SCALE_BUDGET_FRACS = (0.05, 0.10, 0.20, 1.00)

@@ -244,3 +244,40 @@ def make_final_scale_case(cfg: WorkloadConfig, device="cpu", units: Optional[Seq
     kh = torch.where(boosted.unsqueeze(-1), kh + bump, kh)
     return FinalScaleCase(_to_dtype(q, cfg), _to_dtype(kc, cfg), _to_dtype(vc, cfg),
                           _to_dtype(kh, cfg), _to_dtype(vh, cfg), boosted)
+
+
+@dataclass
+class AsiCase:
+    q_samp: torch.Tensor   # [S,H,n_samp,d] sampled queries of the current map
+    k_all: torch.Tensor    # [S,H,hist_len + cur_len,d]: every earlier row, then the current map's keys
+    hist_len: int
+    cur_len: int
+    rows: Tuple[int, ...]  # positions of the sampled queries in the current map
+
+
+def asi_sample_rows(n_k: int, n_samp: int) -> Tuple[int, ...]:
+    """min(n_samp, n_k) query positions spread evenly over the current map (raster order)."""
+    n = min(n_samp, n_k)
+    return tuple((2 * j + 1) * n_k // (2 * n) for j in range(n))
+
+
+def assemble_asi_case(k_history: Sequence[torch.Tensor], q_cur: torch.Tensor, k_cur: torch.Tensor,
+                      n_samp: int = 16) -> AsiCase:
+    """Inputs of the Attention Selectivity Index (Eq. 2) for one (layer, scale) pair from
+    tensors that already exist: k_history = the keys of the prefix and of every earlier map,
+    in cache order; q_cur / k_cur = the current map's queries and keys.  Rows only are moved."""
+    n_k = q_cur.shape[-2]
+    rows = asi_sample_rows(n_k, n_samp)
+    q_samp = q_cur.index_select(-2, torch.tensor(rows, device=q_cur.device)).contiguous()
+    k_all = torch.cat(list(k_history) + [k_cur], dim=-2).contiguous()
+    return AsiCase(q_samp, k_all, k_all.shape[-2] - n_k, n_k, rows)
+
+
+def make_asi_case(cfg: WorkloadConfig, layer: int, scale: int, device="cpu", n_samp: int = 16,
+                  units: Optional[Sequence[int]] = None) -> AsiCase:
+    """The same for a workload config: the uncompressed cache entering `scale` (prefix and maps
+    1..scale-1), the current map's keys behind it, and n_samp of its queries."""
+    hist = [make_prefix(cfg, layer, device, units)[0]]
+    hist += [make_step_inputs(cfg, layer, j, device, units).k_cur for j in range(1, scale)]
+    x = make_step_inputs(cfg, layer, scale, device, units)
+    return assemble_asi_case(hist, x.q, x.k_cur, n_samp)
