@@ -56,11 +56,12 @@ ATTEND_PIPE_TRAFFIC = {
 }
 
 
-VARIANTS = ("scalekv", "literal", "pyramid", "sliding", "sinks")
+VARIANTS = ("scalekv", "literal", "pyramid", "sliding", "sinks", "calibrated")
 # stages between consecutive events of one call, per variant
 STAGES = {
     "scalekv": ("score", "select", "compact", "attend"),
     "pyramid": ("score", "select", "compact", "attend"),
+    "calibrated": ("score", "select", "compact", "attend"),
     "literal": ("append", "attend", "score+select", "compact"),
     "sliding": ("select", "compact", "attend"),
     "sinks": ("select", "compact", "attend"),
@@ -248,8 +249,6 @@ def main() -> int:
     # ---- resident state: prefix caches, ping-pong caches, per-(layer, scale) inputs
     t_setup = time.perf_counter()
     prefix = [W.make_prefix(cfg, l, dev) for l in range(Lyr)]
-    bufs = [[(torch.empty(S, H, cap, d, dtype=dtype, device=dev), torch.empty(S, H, cap, d, dtype=dtype, device=dev))
-             for _ in range(2)] for _ in range(Lyr)]
     inputs = {}
     for k in range(1, K + 1):
         for l in range(Lyr):
@@ -259,6 +258,45 @@ def main() -> int:
                 inputs[(l, k)] = W.make_step_inputs(cfg, l, k, dev)
         torch.cuda.synchronize()
         log(f"inputs for scale {k}/{K} ready ({torch.cuda.memory_allocated() / 2**30:.1f} GiB resident)")
+    calibration = None
+    if args.variant == "calibrated":
+        # Sec. 3.2 on this workload's own tensors: ASI of every (layer, scale) pair on the uncompressed
+        # cache (Eq. 2), the lowest-Z pairs become drafters (Eq. 3), Eq. 4 splits the uniform budget.
+        # Same number of drafter pairs and same mean budget as the seeded drafter/refiner table; the
+        # paper's B_r(0) and delta (600 and 70 at a uniform budget of 650) scaled to this uniform budget.
+        n_samp, top_k = 16, 64
+        b_uni = max(1, int(uniform_frac * W.c_full(cfg, K) + 0.5))
+        b_r0, delta = b_uni * 600 // 650, max(1, (b_uni * 70 * 13) // (650 * K))
+        full_len = W.c_full(cfg, K) + cfg.n_tokens(K)
+        ws_asi = torch.empty(skv.workspace_bytes(shape, full_len, n_samp), dtype=torch.uint8, device=dev)
+        asi_dev = torch.zeros(Lyr, K, 3, dtype=torch.float32, device=dev)
+        t_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        asi_ms = 0.0
+        for l in range(Lyr):
+            hist = [prefix[l][0]]
+            for k in range(1, K + 1):
+                x = inputs[(l, k)]
+                case = W.assemble_asi_case(hist, x.q, x.k_cur, n_samp)
+                terms = torch.empty(S, H, case.q_samp.shape[2], 2, dtype=torch.float32, device=dev)
+                t_ev[0].record()
+                skv.asi(shape, case.q_samp, case.k_all, case.hist_len, case.cur_len, top_k, terms, asi_dev[l, k - 1], ws_asi)
+                t_ev[1].record()
+                torch.cuda.synchronize()
+                asi_ms += t_ev[0].elapsed_time(t_ev[1])
+                hist.append(x.k_cur)
+                del case, terms
+        asi_lk = asi_dev[:, :, 2].double().cpu().tolist()
+        table, roles, b_r, b_d, slack = skv.policy_table(asi_lk, cfg.n_drafter * K, b_uni, b_r0, delta, 0)
+        cap = max(min(table[l][k - 1], W.c_full(cfg, k)) + cfg.n_tokens(k) for l in range(Lyr) for k in range(1, K + 1))
+        calibration = {"pairs": Lyr * K, "queries_per_pair": n_samp, "top_k": top_k, "asi_ms_total": asi_ms,
+                       "b_uniform": b_uni, "b_r0": b_r0, "delta": delta, "b_d": b_d, "b_r": b_r, "slack": slack,
+                       "drafters_per_scale": [sum(roles[l][k] for l in range(Lyr)) for k in range(K)]}
+        log(f"calibration: {Lyr * K} ASI calls {asi_ms:.1f} ms; b_d {b_d}, b_r {b_r}, "
+            f"drafters per scale {calibration['drafters_per_scale']}")
+        del ws_asi, asi_dev
+        torch.cuda.empty_cache()
+    bufs = [[(torch.empty(S, H, cap, d, dtype=dtype, device=dev), torch.empty(S, H, cap, d, dtype=dtype, device=dev))
+             for _ in range(2)] for _ in range(Lyr)]
     max_q = max(cfg.n_tokens(k) for k in range(1, K + 1))
     ws = torch.empty(skv.workspace_bytes(shape, cap, max_q), dtype=torch.uint8, device=dev)
     out = torch.empty(S, H, max_q, d, dtype=dtype, device=dev)
@@ -343,7 +381,7 @@ def main() -> int:
             dst = bufs[l][k % 2]
             m = dict(layer=l, scale=k, cache_len=lens[l], n_cur=n_cur, score_bytes=0.0, append_in_attend=0.0)
             append_bytes = 2.0 * 2.0 * n_cur * d * e * U   # K and V, read + write
-            if variant in ("scalekv", "pyramid"):
+            if variant in ("scalekv", "pyramid", "calibrated"):
                 call = skv.PreparedStep(shape, x.q, x.k_cur, x.v_cur, windows[k], srcs[l][0], srcs[l][1], lens[l],
                                         table[l][k - 1], dst[0], dst[1], outs[k], None, ws)
                 keep = call.new_len - n_cur
@@ -548,6 +586,7 @@ def main() -> int:
             "ms": ms_stage_pass, "stage_ms": stage_ms, "per_scale_ms": per_scale_ms,
             "per_scale_stage_ms": {str(k): [round(x, 4) for x in v] for k, v in per_scale_stage_ms.items()}},
         "standalone_kernels": standalone,
+        "calibration": calibration,
         "hip_graph_replay": None,
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS,
@@ -598,7 +637,7 @@ def main() -> int:
     # ---- the same sequence captured once into a HIP graph and replayed (what a serving loop with
     # fixed shapes would do); reported beside the eager number, never in place of it.  Last GPU
     # work of the run, so that a failed capture cannot disturb any other measurement.
-    if not args.no_graph_pass and variant in ("scalekv", "pyramid", "literal"):
+    if not args.no_graph_pass and variant in ("scalekv", "pyramid", "literal", "calibrated"):
         try:
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
