@@ -438,12 +438,18 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"warm-up {w + 1}/{args.warmup} done")
 
-    # Timed region: K passes of the sequence.  The only events inside it bracket the launches
-    # of the dominant kernel (the pipelined bf16 attention, n_cur > 128); they sit on the launch
-    # stream and give that kernel's average duration for the roofline.
+    # Timed region: K passes of the sequence.  The only events inside it bracket launches of the
+    # dominant kernel (the pipelined bf16 attention, n_cur > 128); they sit on the launch stream
+    # (attached to the kernel's own dispatch) and give that kernel's average duration for the
+    # roofline.  Timing every such launch in every pass costs about 1 % of the pass, so each of them
+    # is timed in exactly one of the K passes (the j-th such launch of the sequence in pass j mod K).
     n_ev = len(stages) + 1
-    ev_steps = [[events.block(n_ev, only=(att, att + 1)) if is_big(m["n_cur"]) else None for m in meta]
-                for _ in range(args.steps)]
+    big_no = {}
+    for i, m in enumerate(meta):
+        if is_big(m["n_cur"]):
+            big_no[i] = len(big_no)
+    ev_steps = [[events.block(n_ev, only=(att, att + 1)) if i in big_no and big_no[i] % args.steps == s else None
+                 for i in range(len(meta))] for s in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):

@@ -286,6 +286,10 @@ scalekv_status scalekv_pyramid_budgets(int32_t n_layer, int64_t b_uniform, int64
  * anyway).  A NULL entry is left out, so {0,0,0,e3,e4} brackets the attend kernel
  * alone.  scalekv_step_append_first records them too: events[0] before the first
  * kernel, events[1..4] after its append, attend, score+select and compact kernels.
+ * Where the attention runs in the pipelined bf16 kernel (head_dim 128, n_cur > 128) the
+ * two events around it are not recorded as stream operations of their own but attached
+ * to that kernel's dispatch and receive its start and end times, so timing that kernel
+ * alone ({0,0,0,e3,e4}) adds nothing to the stream.
  * The array is read at each such call and must stay valid until it is replaced or
  * cleared. */
 scalekv_status scalekv_step_stage_events(void** events);

@@ -406,16 +406,20 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                              view(k_src), view(v_src), idx, keep, k_cur, v_cur,
                              fused_append ? 0 : n_cur, view(k_dst), view(v_dst), st),
               "compact launch");
-  SCALEKV_HIP(mark(3), "event record");
-  if (fused_append)
+  if (fused_append) {
+    // events 3 and 4 ride on this kernel's dispatch: its own start and end
     SCALEKV_HIP(launch_attend_pipe(U, shape->n_head, q, n_cur, view(k_dst), view(v_dst), keep, k_cur,
-                                   v_cur, n_cur, true, resolve_scale(shape), out, st),
+                                   v_cur, n_cur, true, resolve_scale(shape), out, st,
+                                   ev ? static_cast<hipEvent_t>(ev[3]) : nullptr,
+                                   ev ? static_cast<hipEvent_t>(ev[4]) : nullptr),
                 "attend launch");
-  else
+  } else {
+    SCALEKV_HIP(mark(3), "event record");
     SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q, n_cur,
                               view(k_dst), view(v_dst), keep + n_cur, resolve_scale(shape), out, st),
                 "attend launch");
-  SCALEKV_HIP(mark(4), "event record");
+    SCALEKV_HIP(mark(4), "event record");
+  }
   if (new_len_out) *new_len_out = keep + n_cur;
   return SCALEKV_OK;
 }
@@ -547,17 +551,21 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
                                view(v_cache), nullptr, 0, k_cur, v_cur, n_cur, kt, vt, st),
                 "append launch");
   }
-  SCALEKV_HIP(mark(1), "event record");
   // 2. the map attends over history and itself
-  if (fused_append)
+  if (fused_append) {
+    // events 1 and 2 ride on this kernel's dispatch: its own start and end
     SCALEKV_HIP(launch_attend_pipe(U, shape->n_head, q, n_cur, view(k_cache), view(v_cache), cache_len,
-                                   k_cur, v_cur, n_cur, true, resolve_scale(shape), out, st),
+                                   k_cur, v_cur, n_cur, true, resolve_scale(shape), out, st,
+                                   ev ? static_cast<hipEvent_t>(ev[1]) : nullptr,
+                                   ev ? static_cast<hipEvent_t>(ev[2]) : nullptr),
                 "attend launch");
-  else
+  } else {
+    SCALEKV_HIP(mark(1), "event record");
     SCALEKV_HIP(launch_attend(shape->dtype, shape->n_seq, shape->n_head, d, q, n_cur, view(k_cache),
                               view(v_cache), len, resolve_scale(shape), out, st),
                 "attend launch");
-  SCALEKV_HIP(mark(2), "event record");
+    SCALEKV_HIP(mark(2), "event record");
+  }
   if (keep_out) *keep_out = keep;
   if (moved_out) *moved_out = moves ? 1 : 0;
   if (!moves) {  // everything is kept: the cache stays where it is

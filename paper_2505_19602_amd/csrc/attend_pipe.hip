@@ -60,6 +60,8 @@
 // (rows len1 .. len1+len2-1): the append of the pruning step, done here because this
 // kernel is bound by the matrix pipe and leaves the HBM idle, while a separate copy
 // kernel would be bound by the HBM and leave the matrix pipe idle.
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 #include "common.h"
@@ -466,18 +468,26 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
 
 hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
                               int len1, const void* k2, const void* v2, int len2, bool append,
-                              float sm_scale, void* out, hipStream_t stream) {
+                              float sm_scale, void* out, hipStream_t stream, hipEvent_t start,
+                              hipEvent_t stop) {
   static std::atomic<uint64_t> configured{0};
   const hipError_t e = allow_dynamic_lds((const void*)attend_pipe_kernel, kLdsBytes, configured);
   if (e != hipSuccess) return e;
   const float scale_log2e = sm_scale * 1.4426950408889634f;
   const int n_qtile = (n_q + BM - 1) / BM;
   const int n_wg = n_qtile * n_unit;
-  hipLaunchKernelGGL(attend_pipe_kernel, dim3(n_wg), dim3(256), kLdsBytes, stream,
-                     (const uint16_t*)q, n_q, (uint16_t*)const_cast<void*>(k.ptr), k.seq_stride,
-                     k.head_stride, (uint16_t*)const_cast<void*>(v.ptr), v.seq_stride, v.head_stride,
-                     len1, (const uint16_t*)k2, (const uint16_t*)v2, len2, append ? 1 : 0, n_head,
-                     n_qtile, n_wg, scale_log2e, (uint16_t*)out);
+  if (start || stop)
+    hipExtLaunchKernelGGL(attend_pipe_kernel, dim3(n_wg), dim3(256), kLdsBytes, stream, start, stop, 0,
+                          (const uint16_t*)q, n_q, (uint16_t*)const_cast<void*>(k.ptr), k.seq_stride,
+                          k.head_stride, (uint16_t*)const_cast<void*>(v.ptr), v.seq_stride,
+                          v.head_stride, len1, (const uint16_t*)k2, (const uint16_t*)v2, len2,
+                          append ? 1 : 0, n_head, n_qtile, n_wg, scale_log2e, (uint16_t*)out);
+  else
+    hipLaunchKernelGGL(attend_pipe_kernel, dim3(n_wg), dim3(256), kLdsBytes, stream,
+                       (const uint16_t*)q, n_q, (uint16_t*)const_cast<void*>(k.ptr), k.seq_stride,
+                       k.head_stride, (uint16_t*)const_cast<void*>(v.ptr), v.seq_stride,
+                       v.head_stride, len1, (const uint16_t*)k2, (const uint16_t*)v2, len2,
+                       append ? 1 : 0, n_head, n_qtile, n_wg, scale_log2e, (uint16_t*)out);
   return hipGetLastError();
 }
 

@@ -91,10 +91,13 @@ hipError_t launch_attend(int dtype, int n_seq, int n_head, int d, const void* q,
 // bf16, head_dim 128 only: the pipelined kernel used when n_q is large.  Keys and values are the
 // first len1 rows of the caches k, v followed by the len2 rows of the dense tensors k2, v2
 // ([U, len2, d]; may be NULL when len2 == 0).  With `append` the kernel also copies k2, v2 into
-// rows [len1, len1 + len2) of the caches, which must have room for them.
+// rows [len1, len1 + len2) of the caches, which must have room for them.  `start` / `stop`
+// (either may be NULL): events that receive the kernel's own start and end times; they ride on
+// the kernel's dispatch, so unlike hipEventRecord they put no operation of their own on the stream.
 hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, KvView k, KvView v,
                               int len1, const void* k2, const void* v2, int len2, bool append,
-                              float sm_scale, void* out, hipStream_t stream);
+                              float sm_scale, void* out, hipStream_t stream,
+                              hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 // whether launch_attend would take the pipelined kernel for this shape
 inline bool attend_uses_pipe(int dtype, int d, int n_q) { return dtype == 1 && d == 128 && n_q > 128; }
 
