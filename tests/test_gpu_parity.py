@@ -451,6 +451,46 @@ def test_step_edge_budgets(n_cur):
             check_indices(idx.cpu().numpy().reshape(S * H, keep)[u], own["scores"][u], keep, own["idx"][u])
 
 
+def test_step_sweep_of_sizes_around_the_tile_edges():
+    """Seeded sweep of whole steps whose sizes sit on and next to the kernels' tile edges (32-row
+    query blocks, 64-key tiles, 128-row query tiles, 256-key score chunks, the 128-row switch to
+    the pipelined attention kernel), with windows scattered over the map, both dtypes and both
+    head sizes; every unit is followed by the oracle."""
+    rng = np.random.default_rng(20250519)
+    edges_q = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 159, 160, 161, 255, 256, 257, 300]
+    edges_l = [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700]
+    for case in range(36):
+        dtype = torch.bfloat16 if case % 3 else torch.float32
+        d = 128 if case % 2 else 64
+        S, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        n_cur, L = int(rng.choice(edges_q)), int(rng.choice(edges_l))
+        budget = int(rng.choice([0, 1, max(1, L // 3), max(0, L - 1), L, L + 3]))
+        keep = min(budget, L)
+        n_win = int(rng.integers(1, min(16, n_cur) + 1))
+        win = sorted(int(x) for x in rng.choice(n_cur, size=n_win, replace=False))
+        _note(f"sweep case={case} dtype={dtype} d={d} S={S} H={H} n_cur={n_cur} L={L} budget={budget} n_win={n_win}")
+        shape = skv.Shape(S, H, d, dtype)
+        q, kc, vc = (_rand(900 + 7 * case + i, (S, H, n_cur, d), dtype) for i in range(3))
+        ks, vs = (_rand(900 + 7 * case + 3 + i, (S, H, max(L, 1), d), dtype) for i in range(2))
+        ws = torch.empty(skv.workspace_bytes(shape, max(L, 1), n_cur), dtype=torch.uint8, device=DEV)
+        kd = torch.zeros(S, H, keep + n_cur, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
+        out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+        new_len = skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), win, ks.to(DEV), vs.to(DEV), L, budget,
+                           kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        assert new_len == keep + n_cur
+        g_idx = idx.cpu().numpy().reshape(S * H, keep)
+        k_u, v_u = units(ks)[:, :L], units(vs)[:, :L]
+        own = oracle.step(units(q), units(kc), units(vc), win, k_u, v_u, budget)
+        for u in range(S * H):
+            check_indices(g_idx[u], own["scores"][u], keep, own["idx"][u])
+        ref = oracle.step(units(q), units(kc), units(vc), win, k_u, v_u, budget, force_idx=g_idx)
+        assert np.array_equal(units(kd)[:, :new_len].double().numpy(), ref["k_dst"])
+        assert np.array_equal(units(vd)[:, :new_len].double().numpy(), ref["v_dst"])
+        check_output(out, ref["out"], dtype, f"sweep case {case}")
+
+
 def test_step_one_hot_pattern_selects_its_argmax():
     dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 400, 32
     shape = skv.Shape(S, H, d, dtype)
