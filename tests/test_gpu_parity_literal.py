@@ -237,3 +237,51 @@ def test_literal_step_long_cache_uses_the_two_kernel_route():
     assert np.array_equal(units(kn).double().numpy(), ref["k_next"])
     assert np.array_equal(units(vn).double().numpy(), ref["v_next"])
     check_output(units(out), ref["out"], dtype, "literal long cache")
+
+
+def test_literal_step_sweep_of_sizes_around_the_tile_edges():
+    """Seeded sweep of whole literal-order steps whose map and cache sizes sit on and next to the
+    kernels' tile edges, with scattered windows, pooling widths 1..7 and both dtypes / head sizes;
+    every unit is followed by the oracle."""
+    rng = np.random.default_rng(20250520)
+    edges_q = [1, 2, 31, 32, 33, 64, 65, 127, 128, 129, 160, 161, 255, 256, 257]
+    edges_l = [0, 1, 16, 17, 63, 64, 65, 128, 129, 255, 256, 257, 500]
+    for case in range(24):
+        dtype = torch.bfloat16 if case % 3 else torch.float32
+        d = 128 if case % 2 else 64
+        S, H = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        n_cur, L = int(rng.choice(edges_q)), int(rng.choice(edges_l))
+        total = L + n_cur
+        n_win = int(rng.integers(1, min(16, n_cur) + 1))
+        win = sorted(int(x) for x in rng.choice(n_cur, size=n_win, replace=False))
+        budget = int(rng.choice([0, 1, max(1, total // 4), max(0, total - n_win - 1), total - n_win, total + 3]))
+        pool_w = int(rng.choice([1, 3, 5, 7]))
+        keep = n_win + min(budget, total - n_win)
+        _note(f"literal sweep case={case} dtype={dtype} d={d} S={S} H={H} n_cur={n_cur} L={L} budget={budget} "
+              f"n_win={n_win} pool_w={pool_w}")
+        shape = skv.Shape(S, H, d, dtype)
+        q, kc, vc = (_rand(1500 + 7 * case + i, (S, H, n_cur, d), dtype).to(DEV) for i in range(3))
+        ks, vs = (_rand(1500 + 7 * case + 3 + i, (S, H, max(L, 1), d), dtype)[:, :, :L] for i in range(2))
+        k_cache = torch.zeros(S, H, total, d, dtype=dtype, device=DEV); v_cache = torch.zeros_like(k_cache)
+        k_cache[:, :, :L] = ks.to(DEV); v_cache[:, :, :L] = vs.to(DEV)
+        k_next = torch.zeros(S, H, total, d, dtype=dtype, device=DEV); v_next = torch.zeros_like(k_next)
+        ws = torch.empty(skv.workspace_bytes(shape, total, n_cur), dtype=torch.uint8, device=DEV)
+        out = torch.empty(S, H, n_cur, d, dtype=dtype, device=DEV)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+        got_keep, moved = skv.step_append_first(shape, q, kc, vc, win, pool_w, k_cache, v_cache, L, budget,
+                                                k_next, v_next, out, idx, ws)
+        torch.cuda.synchronize()
+        assert got_keep == keep and moved == (keep < total)
+        g_idx = idx.cpu().numpy().reshape(S * H, keep)
+        own = oracle.step_append_first(units(q), units(kc), units(vc), win, units(ks), units(vs), budget, pool_w=pool_w)
+        assert own["keep"] == keep
+        forced = [L + w for w in win]
+        for u in range(S * H):
+            check_window_indices(g_idx[u], own["scores"][u], forced, budget, own["idx"][u])
+        ref = oracle.step_append_first(units(q), units(kc), units(vc), win, units(ks), units(vs), budget,
+                                       pool_w=pool_w, force_idx=g_idx)
+        assert torch.equal(k_cache[:, :, L:], kc) and torch.equal(v_cache[:, :, L:], vc)
+        held_k, held_v = (k_next, v_next) if moved else (k_cache, v_cache)
+        assert np.array_equal(units(held_k)[:, :keep].double().numpy(), ref["k_next"])
+        assert np.array_equal(units(held_v)[:, :keep].double().numpy(), ref["v_next"])
+        check_output(units(out), ref["out"], dtype, f"literal sweep case {case}")
