@@ -121,8 +121,9 @@ def step(q, k_cur, v_cur, win_idx: Sequence[int], k_src, v_src, budget: int,
          scale: Optional[float] = None, force_idx=None):
     """One (layer, scale) call: score -> select -> compact (+append) -> attend.
     q/k_cur/v_cur [U, n_cur, d]; k_src/v_src [U, cache_len, d].
-    Returns dict(k_dst, v_dst [U, keep+n_cur, d], idx [U, keep], scores
-    [U, cache_len], out [U, n_cur, d], new_len)."""
+    Returns dict(k_dst, v_dst [U, keep+n_cur, d], idx [U, keep], scores and
+    log_scores [U, cache_len], out [U, n_cur, d], new_len).  The selection ranks
+    on the log-scores."""
     q, k_cur, v_cur, k_src, v_src = map(_f64, (q, k_cur, v_cur, k_src, v_src))
     U, n_cur, d = q.shape
     L = k_src.shape[1]
@@ -135,12 +136,12 @@ def step(q, k_cur, v_cur, win_idx: Sequence[int], k_src, v_src, budget: int,
         keep = fidx.shape[1]
     k_dst = np.zeros((U, keep + n_cur, d)); v_dst = np.zeros((U, keep + n_cur, d))
     idx = np.zeros((U, keep), dtype=np.int32)
-    sc = np.zeros((U, L)); out = np.zeros((U, n_cur, d))
+    sc = np.zeros((U, L)); lsc = np.zeros((U, L)); out = np.zeros((U, n_cur, d))
     lib().scalekv_oracle_step_batch(
         U, _dp(q), _dp(k_cur), _dp(v_cur), n_cur, _ip(win), len(win), _dp(k_src), _dp(v_src), L,
         int(budget), d, ctypes.c_double(scale), _ip(fidx), keep if fidx is not None else 0,
-        _dp(k_dst), _dp(v_dst), _ip(idx), _dp(sc), _dp(out))
-    return dict(k_dst=k_dst, v_dst=v_dst, idx=idx, scores=sc, out=out, new_len=keep + n_cur)
+        _dp(k_dst), _dp(v_dst), _ip(idx), _dp(sc), _dp(lsc), _dp(out))
+    return dict(k_dst=k_dst, v_dst=v_dst, idx=idx, scores=sc, log_scores=lsc, out=out, new_len=keep + n_cur)
 
 
 def cache_lengths(prefix: int, n_tok: Sequence[int], budget: Sequence[int]) -> Tuple[np.ndarray, np.ndarray, int]:
@@ -172,6 +173,16 @@ def pool(scores, pool_w: int) -> np.ndarray:
     return out
 
 
+def pool_log(log_scores, pool_w: int) -> np.ndarray:
+    """The same pooling on log-scores: log of the average of exp(log_scores) over the window,
+    finite where the scores themselves underflow. [U, len] -> [U, len]."""
+    ls = _f64(log_scores)
+    out = np.zeros_like(ls)
+    for u in range(ls.shape[0]):
+        lib().scalekv_oracle_pool_log(_dp(ls[u]), ls.shape[1], int(pool_w), _dp(out[u]))
+    return out
+
+
 def select_forced(scores, budget: int, forced: Sequence[int]) -> np.ndarray:
     """Forced positions plus the top-min(budget, rest) of the others, ascending.
     scores [U, len] -> idx [U, keep]."""
@@ -191,7 +202,7 @@ def step_append_first(q, k_cur, v_cur, win_idx: Sequence[int], k_cache, v_cache,
                       pool_w: int = 1, scale: Optional[float] = None, force_idx=None):
     """One (layer, scale) call in the order of Sec. 3.3: append -> attend ->
     score over history and current map -> pool -> keep window + top-budget.
-    Returns dict(out [U, n_cur, d], scores [U, len], idx [U, keep],
+    Returns dict(out [U, n_cur, d], scores and log_scores [U, len] (pooled), idx [U, keep],
     k_next, v_next [U, keep, d], keep) with len = cache_len + n_cur."""
     q, k_cur, v_cur, k_cache, v_cache = map(_f64, (q, k_cur, v_cur, k_cache, v_cache))
     U, n_cur, d = q.shape
@@ -205,12 +216,12 @@ def step_append_first(q, k_cur, v_cur, win_idx: Sequence[int], k_cache, v_cache,
         fkeep = fidx.shape[1]
     k_next = np.zeros((U, n, d)); v_next = np.zeros((U, n, d))
     idx = np.zeros((U, n), dtype=np.int32)
-    sc = np.zeros((U, n)); out = np.zeros((U, n_cur, d))
+    sc = np.zeros((U, n)); lsc = np.zeros((U, n)); out = np.zeros((U, n_cur, d))
     keep = lib().scalekv_oracle_step_append_first_batch(
         U, _dp(q), _dp(k_cur), _dp(v_cur), n_cur, _ip(win), len(win), int(pool_w), _dp(k_cache),
         _dp(v_cache), L, int(budget), d, ctypes.c_double(scale), _ip(fidx), fkeep, _dp(k_next),
-        _dp(v_next), _ip(idx), _dp(sc), _dp(out))
-    return dict(out=out, scores=sc, idx=idx[:, :keep].copy(), k_next=k_next[:, :keep].copy(),
+        _dp(v_next), _ip(idx), _dp(sc), _dp(lsc), _dp(out))
+    return dict(out=out, scores=sc, log_scores=lsc, idx=idx[:, :keep].copy(), k_next=k_next[:, :keep].copy(),
                 v_next=v_next[:, :keep].copy(), keep=int(keep))
 
 

@@ -176,7 +176,15 @@ void scalekv_oracle_attend(const double* q, int n_q, const double* k, const doub
  * cache_len rows; k_dst/v_dst receive keep + n_cur rows; idx receives keep
  * indices; out receives n_cur rows.  budget >= cache_len keeps every row
  * (then the result is plain attention over the whole cache and the current
- * map).  If force_idx is non-NULL, its force_keep entries are used in place of
+ * map).
+ * The ranking of Sec. 3.3 ("the top-k^l tokens with the highest aggregated
+ * importance scores") only depends on the order of the scores, and log is
+ * strictly increasing, so the selection is taken on log s_i: the same order
+ * wherever s_i is representable, and still an order where s_i itself would
+ * underflow to zero (sharply peaked rows), where ranking on s_i would see a
+ * tie that Eq. 5 does not contain.
+ * score_out / log_score_out (each may be NULL) receive s_i and log s_i.
+ * If force_idx is non-NULL, its force_keep entries are used in place of
  * the oracle's own selection (lets a test follow the GPU's choice at a near-tie
  * so later scales stay comparable).  Returns the new cache length.
  */
@@ -184,25 +192,29 @@ int scalekv_oracle_step(const double* q, const double* k_cur, const double* v_cu
                         const int32_t* win_idx, int n_win, const double* k_src,
                         const double* v_src, int cache_len, int budget, int d, double scale,
                         const int32_t* force_idx, int force_keep, double* k_dst, double* v_dst,
-                        int32_t* idx, double* score_out, double* out) {
+                        int32_t* idx, double* score_out, double* log_score_out, double* out) {
   int keep = budget < cache_len ? budget : cache_len;
   if (keep < 0) keep = 0;
-  double* s = (double*)malloc((size_t)(cache_len > 0 ? cache_len : 1) * sizeof(double));
+  size_t n_s = (size_t)(cache_len > 0 ? cache_len : 1);
+  double* s = (double*)malloc(n_s * sizeof(double));
+  double* log_s = (double*)malloc(n_s * sizeof(double));
   double* qw = (double*)malloc((size_t)(n_win > 0 ? n_win : 1) * d * sizeof(double));
   for (int j = 0; j < n_win; ++j)
     memcpy(qw + (size_t)j * d, q + (size_t)win_idx[j] * d, (size_t)d * sizeof(double));
-  scalekv_oracle_score(qw, n_win, k_src, cache_len, d, scale, s, NULL, NULL);
+  scalekv_oracle_score(qw, n_win, k_src, cache_len, d, scale, s, log_s, NULL);
   if (score_out) memcpy(score_out, s, (size_t)cache_len * sizeof(double));
+  if (log_score_out) memcpy(log_score_out, log_s, (size_t)cache_len * sizeof(double));
   if (force_idx) {
     keep = force_keep;
     memcpy(idx, force_idx, (size_t)keep * sizeof(int32_t));
   } else {
-    keep = scalekv_oracle_select(s, cache_len, budget, idx);
+    keep = scalekv_oracle_select(log_s, cache_len, budget, idx);
   }
   scalekv_oracle_compact(k_src, idx, keep, k_cur, n_cur, d, k_dst);
   int new_len = scalekv_oracle_compact(v_src, idx, keep, v_cur, n_cur, d, v_dst);
   scalekv_oracle_attend(q, n_cur, k_dst, v_dst, new_len, d, scale, out);
   free(s);
+  free(log_s);
   free(qw);
   return new_len;
 }
@@ -211,15 +223,6 @@ int scalekv_oracle_step(const double* q, const double* k_cur, const double* v_cu
  * Units are independent; these only distribute units over host threads.
  * Every per-unit tensor of unit u starts at u * (rows * d) of its array.
  */
-void scalekv_oracle_score_batch(int n_unit, const double* qw, int n_win, const double* k, int len,
-                                int d, double scale, double* s, double* log_s) {
-#pragma omp parallel for schedule(dynamic)
-  for (int u = 0; u < n_unit; ++u)
-    scalekv_oracle_score(qw + (size_t)u * n_win * d, n_win, k + (size_t)u * len * d, len, d, scale,
-                         s ? s + (size_t)u * len : NULL, log_s ? log_s + (size_t)u * len : NULL,
-                         NULL);
-}
-
 void scalekv_oracle_attend_batch(int n_unit, const double* q, int n_q, const double* k,
                                  const double* v, int kv_len, int d, double scale, double* out) {
 #pragma omp parallel for schedule(dynamic)
@@ -233,7 +236,7 @@ void scalekv_oracle_step_batch(int n_unit, const double* q, const double* k_cur,
                                const double* k_src, const double* v_src, int cache_len, int budget,
                                int d, double scale, const int32_t* force_idx, int force_keep,
                                double* k_dst, double* v_dst, int32_t* idx, double* score_out,
-                               double* out) {
+                               double* log_score_out, double* out) {
   int keep = budget < cache_len ? budget : cache_len;
   if (keep < 0) keep = 0;
   if (force_idx) keep = force_keep;
@@ -248,6 +251,7 @@ void scalekv_oracle_step_batch(int n_unit, const double* q, const double* k_cur,
                         k_dst + u * new_len * d, v_dst + u * new_len * d,
                         idx + (size_t)u * (keep > 0 ? keep : 0),
                         score_out ? score_out + (size_t)u * cache_len : NULL,
+                        log_score_out ? log_score_out + (size_t)u * cache_len : NULL,
                         out + (size_t)u * n_cur * d);
 }
 

@@ -87,6 +87,28 @@ void scalekv_oracle_pool(const double* s, int len, int pool_w, double* out) {
   }
 }
 
+/* The same average formed on log-scores: out_i = log( (1/pool_w) * sum_t exp(ls_{i+t}) ),
+ * positions beyond the ends contributing zero (log-score -inf).  Written with the window's
+ * largest term taken out of the sum, so that the result stays finite where exp(ls) itself
+ * is not representable; it is the logarithm of what scalekv_oracle_pool returns.
+ */
+void scalekv_oracle_pool_log(const double* ls, int len, int pool_w, double* out) {
+  int r = (pool_w - 1) / 2;
+  for (int i = 0; i < len; ++i) {
+    double top = -INFINITY;
+    for (int t = -r; t <= r; ++t)
+      if (i + t >= 0 && i + t < len && ls[i + t] > top) top = ls[i + t];
+    if (!(top > -INFINITY)) {
+      out[i] = -INFINITY;
+      continue;
+    }
+    double acc = 0.0;
+    for (int t = -r; t <= r; ++t)
+      if (i + t >= 0 && i + t < len) acc += exp(ls[i + t] - top);
+    out[i] = top + log(acc) - log((double)pool_w);
+  }
+}
+
 /* ------------------------------------------------- selection with a window --
  * The forced positions (the observation window) are preserved whatever their
  * score; of the remaining len - n_forced tokens the min(budget, len - n_forced)
@@ -130,16 +152,19 @@ int scalekv_oracle_select_forced(const double* score, int len, int budget, const
  * k_cache/v_cache: cache_len rows; q/k_cur/v_cur: n_cur rows; window rows are
  * win_idx[0..n_win) of the current map, i.e. cache positions cache_len +
  * win_idx[j].  k_next/v_next and idx must hold cache_len + n_cur rows /
- * entries.  score_out (optional) receives the pooled scores of all cache_len +
- * n_cur positions.  If force_idx is non-NULL its force_keep entries replace the
- * oracle's own selection.  Returns the number of rows kept.
+ * entries.  score_out / log_score_out (optional) receive the pooled scores of all
+ * cache_len + n_cur positions and their logarithms.  The ranking is taken on the
+ * logarithms: the order Sec. 3.3 asks for is unchanged by a strictly increasing map,
+ * and the logarithm stays finite where a sharply peaked row's score underflows.
+ * If force_idx is non-NULL its force_keep entries replace the oracle's own selection.
+ * Returns the number of rows kept.
  */
 int scalekv_oracle_step_append_first(const double* q, const double* k_cur, const double* v_cur,
                                      int n_cur, const int32_t* win_idx, int n_win, int pool_w,
                                      const double* k_cache, const double* v_cache, int cache_len,
                                      int budget, int d, double scale, const int32_t* force_idx,
                                      int force_keep, double* k_next, double* v_next, int32_t* idx,
-                                     double* score_out, double* out) {
+                                     double* score_out, double* log_score_out, double* out) {
   int len = cache_len + n_cur;
   size_t row = (size_t)d * sizeof(double);
   double* k_all = (double*)malloc((size_t)(len > 0 ? len : 1) * row);
@@ -159,16 +184,20 @@ int scalekv_oracle_step_append_first(const double* q, const double* k_cur, const
   }
   double* s = (double*)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
   double* sp = (double*)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
-  scalekv_oracle_score(qw, n_win, k_all, len, d, scale, s, NULL, NULL);
+  double* ls = (double*)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
+  double* lsp = (double*)malloc((size_t)(len > 0 ? len : 1) * sizeof(double));
+  scalekv_oracle_score(qw, n_win, k_all, len, d, scale, s, ls, NULL);
   scalekv_oracle_pool(s, len, pool_w, sp);
+  scalekv_oracle_pool_log(ls, len, pool_w, lsp);
   if (score_out) memcpy(score_out, sp, (size_t)len * sizeof(double));
+  if (log_score_out) memcpy(log_score_out, lsp, (size_t)len * sizeof(double));
 
   int keep;
   if (force_idx) {
     keep = force_keep;
     memcpy(idx, force_idx, (size_t)keep * sizeof(int32_t));
   } else {
-    keep = scalekv_oracle_select_forced(sp, len, budget, forced, n_win, idx);
+    keep = scalekv_oracle_select_forced(lsp, len, budget, forced, n_win, idx);
   }
   for (int t = 0; t < keep; ++t) {
     memcpy(k_next + (size_t)t * d, k_all + (size_t)idx[t] * d, row);
@@ -180,6 +209,8 @@ int scalekv_oracle_step_append_first(const double* q, const double* k_cur, const
   free(forced);
   free(s);
   free(sp);
+  free(ls);
+  free(lsp);
   return keep;
 }
 
@@ -192,7 +223,8 @@ int scalekv_oracle_step_append_first_batch(int n_unit, const double* q, const do
                                            const double* v_cache, int cache_len, int budget, int d,
                                            double scale, const int32_t* force_idx, int force_keep,
                                            double* k_next, double* v_next, int32_t* idx,
-                                           double* score_out, double* out) {
+                                           double* score_out, double* log_score_out,
+                                           double* out) {
   size_t len = (size_t)cache_len + n_cur;
   int keep_all = 0;
 #pragma omp parallel for schedule(dynamic)
@@ -203,7 +235,7 @@ int scalekv_oracle_step_append_first_batch(int n_unit, const double* q, const do
         v_cache + (size_t)u * cache_len * d, cache_len, budget, d, scale,
         force_idx ? force_idx + (size_t)u * force_keep : NULL, force_keep, k_next + u * len * d,
         v_next + u * len * d, idx + u * len, score_out ? score_out + u * len : NULL,
-        out + (size_t)u * n_cur * d);
+        log_score_out ? log_score_out + u * len : NULL, out + (size_t)u * n_cur * d);
     if (u == 0) keep_all = kp;
   }
   return keep_all;

@@ -240,6 +240,40 @@ def test_step_one_hot_pattern_selects_its_argmax_and_uses_window_rows():
     np.testing.assert_allclose(r["out"], _sdpa(q, r["k_dst"], r["v_dst"]), atol=1e-12)
 
 
+def test_step_ranks_on_log_scores_same_choice_where_nothing_underflows():
+    # Sec. 3.3's top-k depends only on the order of the scores; log is strictly increasing, so the
+    # step (which ranks log s) must choose what a ranking of s itself chooses.  Independent check:
+    # the linear scores come from a library softmax, the choice from a full sort.
+    rng = np.random.default_rng(41)
+    for trial in range(20):
+        n_cur, L, d, budget = 6, int(rng.integers(8, 60)), 12, int(rng.integers(1, 8))
+        q, kc, vc = (rng.standard_normal((2, n_cur, d)) * 2 for _ in range(3))
+        ks, vs = rng.standard_normal((2, L, d)) * 2, rng.standard_normal((2, L, d))
+        win = [1, 4, 5]
+        r = oracle.step(q, kc, vc, win, ks, vs, budget)
+        for u in range(2):
+            lib = torch.softmax(torch.from_numpy(q[u][win] @ ks[u].T) / math.sqrt(d), dim=-1).sum(0).numpy()
+            assert lib.min() > 1e-200                                     # nothing underflows here
+            assert r["idx"][u].tolist() == _brute(lib.tolist(), budget), trial
+            np.testing.assert_allclose(r["log_scores"][u], np.log(lib), rtol=0, atol=1e-11)
+        assert np.array_equal(oracle.select(r["scores"], budget), oracle.select(r["log_scores"], budget))
+
+
+def test_step_still_ranks_where_the_scores_underflow():
+    # One window row and logits thousands apart: every score but the largest is 0.0 in fp64, and a
+    # ranking of s would fall back on the index order.  With one row log s_i = logit_i - log Z, so
+    # the order Eq. 5 defines is the order of the dot products, which numpy gives independently.
+    rng = np.random.default_rng(42)
+    n_cur, L, d, budget = 3, 40, 8, 9
+    q, kc, vc = (rng.standard_normal((1, n_cur, d)) for _ in range(3))
+    ks, vs = rng.standard_normal((1, L, d)) * 2000.0, rng.standard_normal((1, L, d))
+    r = oracle.step(q, kc, vc, [2], ks, vs, budget, scale=1.0)
+    assert np.count_nonzero(r["scores"][0]) < budget                       # the regime is the intended one
+    logits = ks[0] @ q[0, 2]
+    assert r["idx"][0].tolist() == _brute(logits.tolist(), budget)
+    assert np.all(np.isfinite(r["log_scores"]))
+
+
 def test_step_forced_indices_are_followed():
     rng = np.random.default_rng(13)
     q, kc, vc = (rng.standard_normal((1, 4, 8)) for _ in range(3))

@@ -2,6 +2,8 @@
 over history and the current map, pool, keep window + top-budget): closed forms,
 library routines, brute force on tiny inputs, hand-built cases.  None retypes
 the oracle's loops."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -78,6 +80,35 @@ def test_pool_constant_scores_closed_form():
     # zeros beyond both ends, divisor always pool_w: edges see (r + 1 + i) / w of the constant
     out = oracle.pool(np.full((1, 10), 3.0), 5)[0]
     np.testing.assert_allclose(out, [3 * 3 / 5, 3 * 4 / 5] + [3.0] * 6 + [3 * 4 / 5, 3 * 3 / 5], atol=1e-15)
+
+
+def test_pool_log_is_the_logarithm_of_the_pooled_scores_and_survives_underflow():
+    rng = np.random.default_rng(3)
+    s = rng.random((2, 41)) + 1e-3
+    for w in (1, 3, 7, 31):
+        np.testing.assert_allclose(oracle.pool_log(np.log(s), w), np.log(oracle.pool(s, w)), rtol=0, atol=1e-13)
+    # log-scores far below what exp() can represent: shifting all of them by a constant shifts the
+    # pooled value by the same constant (the average is homogeneous), so the result is known from a
+    # representable case
+    ls = np.log(s) - 5000.0
+    assert np.all(np.exp(ls) == 0.0)
+    np.testing.assert_allclose(oracle.pool_log(ls, 5), np.log(oracle.pool(s, 5)) - 5000.0, rtol=0, atol=1e-9)
+    # a window that holds nothing but zero scores stays at log 0
+    ls2 = np.full((1, 9), -np.inf); ls2[0, 8] = 0.0
+    out = oracle.pool_log(ls2, 3)[0]
+    assert np.all(np.isneginf(out[:7])) and np.isclose(out[7], -math.log(3.0)) and np.isclose(out[8], -math.log(3.0))
+
+
+def test_literal_step_ranks_on_pooled_log_scores_same_choice_as_pooled_scores():
+    rng = np.random.default_rng(27)
+    for trial in range(10):
+        q, kc, vc, ks, vs = _rand_case(100 + trial)
+        budget, w = int(rng.integers(1, 9)), int(rng.choice([1, 3, 5]))
+        r = oracle.step_append_first(q, kc, vc, [4], ks, vs, budget, pool_w=w)
+        L = ks.shape[1]
+        want = oracle.select_forced(r["scores"], budget, [L + 4])
+        assert np.array_equal(r["idx"], want)
+        np.testing.assert_allclose(r["log_scores"], np.log(r["scores"]), rtol=0, atol=1e-12)
 
 
 # ------------------------------------------------- selection with a window --
