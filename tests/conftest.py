@@ -27,3 +27,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """How the bf16 output rule was used by the parity tests that ran (see parity_util.check_output)."""
+    try:
+        from parity_util import STATS
+    except Exception:
+        return
+    if STATS["bf16_elements"]:
+        terminalreporter.write_line(
+            f"bf16 outputs compared: {STATS['bf16_elements']}; held to 2e-2: all below 8 in magnitude "
+            f"(largest error {STATS['bf16_max_err_below_8']:.3e}); at or above 8: {STATS['bf16_wide']} "
+            f"(largest error {STATS['bf16_wide_max_err']:.3e})")

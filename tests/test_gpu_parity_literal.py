@@ -63,8 +63,7 @@ def test_select_window_matches_oracle(L, budget, n_forced, pool_w, kind):
     got_keep = skv.select_window(shape, ls.to(DEV), L, budget, forced, pool_w, idx)
     torch.cuda.synchronize()
     assert got_keep == keep
-    lin = np.exp(ls.double().numpy().reshape(S * H, L))          # the scores whose logs the GPU was given
-    pooled = oracle.pool(lin, pool_w)
+    pooled = oracle.pool_log(ls.double().numpy().reshape(S * H, L), pool_w)   # log of the pooled scores
     want = oracle.select_forced(pooled, budget, forced)
     got = idx.cpu().numpy().reshape(S * H, keep)
     for u in range(S * H):
@@ -76,7 +75,9 @@ def test_select_window_matches_oracle(L, budget, n_forced, pool_w, kind):
 
 # ------------------------------------------------------------ the literal step --
 
-def _run_literal_chain(cfg, layers, unit_ids, check_all_units, pool_w, last_scale=None):
+def _run_literal_chain(cfg, layers, unit_ids, check_all_units, pool_w, last_scale=None, keep_all_before_first=False):
+    """keep_all_before_first: scales before the first compressed one keep the map as well (the
+    budget rule of the bench's literal variant); otherwise the table's budget is used as it is."""
     dtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     S, H, d = cfg.n_seq, cfg.n_head, cfg.head_dim
     shape = skv.Shape(S, H, d, dtype)
@@ -99,6 +100,8 @@ def _run_literal_chain(cfg, layers, unit_ids, check_all_units, pool_w, last_scal
         for k in range(1, K + 1):
             side = cfg.sides[k - 1]
             n_cur, budget = cfg.n_tokens(k), table[layer][k - 1]
+            if keep_all_before_first and k < cfg.first_compressed_scale:
+                budget = W.c_full(cfg, k) + n_cur
             win = skv.window_centroids(side, side, 4, 4)
             assert win == oracle.window_centroids(side, side, 4, 4).tolist()
             _note(f"literal step cfg={cfg.name} layer={layer} scale={k} cache_len={cache_len} budget={budget} "
@@ -116,11 +119,15 @@ def _run_literal_chain(cfg, layers, unit_ids, check_all_units, pool_w, last_scal
             assert got_keep == keep and moved == (keep < total)
             g_idx = idx.cpu().numpy().reshape(S * H, keep)[u_sel]
             q_u, kc_u, vc_u = (units(t)[u_sel] for t in (x.q, x.k_cur, x.v_cur))
-            own = oracle.step_append_first(q_u, kc_u, vc_u, win, ref_k, ref_v, budget, pool_w=pool_w)
-            assert own["keep"] == keep
+            # the oracle's own choice from its score, pooling and selection stages (the attention, the
+            # expensive part, is computed once, below, on the choice that is followed)
             forced = [cache_len + w for w in win]
+            _, own_ls = oracle.score(q_u[:, win], np.concatenate([ref_k, kc_u.double().numpy()], 1))
+            own_ls = oracle.pool_log(own_ls, pool_w)
+            own_idx = oracle.select_forced(own_ls, budget, forced)
+            assert own_idx.shape[1] == keep
             for i in range(len(u_sel)):
-                stats[check_window_indices(g_idx[i], own["scores"][i], forced, budget, own["idx"][i])] += 1
+                stats[check_window_indices(g_idx[i], own_ls[i], forced, budget, own_idx[i])] += 1
             ref = oracle.step_append_first(q_u, kc_u, vc_u, win, ref_k, ref_v, budget, pool_w=pool_w, force_idx=g_idx)
             # the appended rows are in place, bit-exact, whether or not anything was dropped
             assert np.array_equal(units(k_cache)[u_sel, cache_len:total].double().numpy(), kc_u.double().numpy())
@@ -153,6 +160,17 @@ def test_literal_chain_2b_512_sampled_units(pool_w):
     stats = _run_literal_chain(cfg, [0, 17], [0, 5, 15], False, pool_w)
     _note(f"literal 2b_512 pool_w={pool_w}: {stats}")
     assert stats["exact"] > 0 and stats["moved"] >= 14
+
+
+def test_literal_chain_2b_1024_full_size_sampled_units():
+    """The literal order at the size and in the configuration `bench.py --variant literal` times:
+    workload 2b_1024 on all 256 units, all 13 scales of one layer, 4x4 patch-centroid window, pooling
+    width 7, nothing dropped before the first compressed scale; two units followed by the oracle."""
+    cfg = W.get_config("2b_1024")
+    stats = _run_literal_chain(cfg, [5], [3, 200], False, 7, keep_all_before_first=True)
+    _note(f"literal 2b_1024 pool_w=7: {stats}")
+    assert stats["exact"] + stats["band"] == cfg.n_scale * 2
+    assert stats["moved"] == cfg.n_scale - cfg.first_compressed_scale + 1
 
 
 def test_literal_step_edge_cases():
@@ -231,7 +249,7 @@ def test_literal_step_long_cache_uses_the_two_kernel_route():
     own = oracle.step_append_first(units(q), units(kc), units(vc), win, units(ks), units(vs), budget, pool_w=pool_w)
     g_idx = idx.cpu().numpy().reshape(S * H, keep)
     for u in range(S * H):
-        check_window_indices(g_idx[u], own["scores"][u], [L + w for w in win], budget, own["idx"][u])
+        check_window_indices(g_idx[u], own["log_scores"][u], [L + w for w in win], budget, own["idx"][u])
     ref = oracle.step_append_first(units(q), units(kc), units(vc), win, units(ks), units(vs), budget, pool_w=pool_w,
                                    force_idx=g_idx)
     assert np.array_equal(units(kn).double().numpy(), ref["k_next"])
@@ -277,7 +295,7 @@ def test_literal_step_sweep_of_sizes_around_the_tile_edges():
         assert own["keep"] == keep
         forced = [L + w for w in win]
         for u in range(S * H):
-            check_window_indices(g_idx[u], own["scores"][u], forced, budget, own["idx"][u])
+            check_window_indices(g_idx[u], own["log_scores"][u], forced, budget, own["idx"][u])
         ref = oracle.step_append_first(units(q), units(kc), units(vc), win, units(ks), units(vs), budget,
                                        pool_w=pool_w, force_idx=g_idx)
         assert torch.equal(k_cache[:, :, L:], kc) and torch.equal(v_cache[:, :, L:], vc)
