@@ -20,9 +20,9 @@
  * Conventions common to every entry point
  * ---------------------------------------
  * Memory.  Every pointer is DEVICE memory unless its comment says "host".  All
- *   buffers are allocated, owned and freed by the caller; the library holds no
- *   device state and allocates nothing.  Device pointers must be 16-byte
- *   aligned.
+ *   buffers are allocated, owned and freed by the caller; the library allocates
+ *   nothing and holds no device state apart from the fixed scratch array of
+ *   scalekv_step_static.  Device pointers must be 16-byte aligned.
  * Layout.  Dense tensors are row-major [n_seq, n_head, rows, head_dim] with no
  *   padding.  A cache (scalekv_kv) is [n_seq, n_head, capacity, head_dim] with
  *   explicit sequence and head strides (in elements) and a contiguous row of
@@ -141,6 +141,29 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
                             int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
                             const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
                             int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/* For callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same step as
+ * scalekv_step, same arguments minus ws / ws_bytes, same kernels and bit-identical results;
+ * the score / select scratch lives in an array of SCALEKV_STATIC_SCRATCH_BYTES that is part of
+ * the library's device code (each GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates nothing and frees nothing.  The array's device address
+ * is looked up on the first call on each device (a query, not an allocation); make that
+ * first call outside graph capture.
+ * Limit: shapes whose scalekv_workspace_bytes(shape, cache_len, n_cur) exceeds
+ * SCALEKV_STATIC_SCRATCH_BYTES -> SCALEKV_ERR_WORKSPACE, nothing launched (calls that need no
+ * ranking, budget >= cache_len or budget == 0, use no scratch and are never refused for size).
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same
+ * GPU (different streams or threads) race on it; serialise them or use scalekv_step with
+ * separate workspaces.  Nothing in the array has to be cleared between calls.
+ * Other errors as scalekv_step. */
+#define SCALEKV_STATIC_SCRATCH_BYTES (64u << 20)
+scalekv_status scalekv_step_static(const scalekv_shape* shape, const void* q, const void* k_cur,
+                                   const void* v_cur, int32_t n_cur, const int32_t* win_idx,
+                                   int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
+                                   int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
+                                   const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
+                                   int32_t* idx_out, void* stream);
 
 /* ---- Sec. 3.3 read literally: the map's K/V join the cache, the map attends, and only
  * then is the cache pruned, with the observation window preserved. ---- */

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     compact,
     attend,
     step,
+    step_static,
     PreparedStep,
     PreparedAppendFirst,
     step_stage_events,
@@ -33,5 +34,6 @@ from .binding import (  # noqa: F401
     MAX_WINDOW,
     MAX_ASI_SAMPLES,
     MAX_POOL,
+    STATIC_SCRATCH_BYTES,
     EXPORTED_SYMBOLS,
 )

@@ -19,11 +19,12 @@ MAX_WINDOW = 16
 
 MAX_POOL = 31
 MAX_ASI_SAMPLES = 1024
+STATIC_SCRATCH_BYTES = 64 << 20   # SCALEKV_STATIC_SCRATCH_BYTES
 
 # status-returning entry points first, then the two that return strings
 _STATUS_SYMBOLS = (
     "scalekv_workspace_bytes", "scalekv_score", "scalekv_select", "scalekv_compact",
-    "scalekv_attend", "scalekv_step", "scalekv_step_stage_events",
+    "scalekv_attend", "scalekv_step", "scalekv_step_static", "scalekv_step_stage_events",
     "scalekv_window_centroids", "scalekv_select_window", "scalekv_step_append_first",
     "scalekv_asi", "scalekv_drafter_set", "scalekv_allocate_budgets", "scalekv_select_positional",
     "scalekv_pyramid_budgets", "scalekv_policy_table",
@@ -228,6 +229,31 @@ def step(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor
                               int(len(win_idx)), ctypes.byref(a), ctypes.byref(b), int(cache_len), int(budget),
                               ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len), _ptr(out), _ptr(idx_out),
                               wp, wb, _stream()))
+    return int(new_len.value)
+
+
+def step_static(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor,
+                win_idx: Sequence[int], k_src: torch.Tensor, v_src: torch.Tensor, cache_len: int, budget: int,
+                k_dst: torch.Tensor, v_dst: torch.Tensor, out: torch.Tensor,
+                idx_out: Optional[torch.Tensor]) -> int:
+    """scalekv_step_static: the step with the library's own fixed scratch array instead of a
+    caller workspace (allocates nothing); returns the new cache length."""
+    n_cur = q.shape[2]
+    _dense(q, shape, n_cur, "q"); _dense(k_cur, shape, n_cur, "k_cur"); _dense(v_cur, shape, n_cur, "v_cur")
+    _dense(out, shape, n_cur, "out")
+    if idx_out is not None and (idx_out.dtype != torch.int32 or not idx_out.is_cuda or not idx_out.is_contiguous()
+                                or idx_out.dim() != 3 or tuple(idx_out.shape[:2]) != (shape.n_seq, shape.n_head)):
+        raise ScaleKVError(1, "idx_out must be a contiguous int32 device tensor [S,H,keep]")
+    win = (ctypes.c_int32 * max(1, len(win_idx)))(*[int(w) for w in win_idx])
+    cs = shape.c()
+    a, b, c, d = _kv(k_src, shape, "k_src"), _kv(v_src, shape, "v_src"), _kv(k_dst, shape, "k_dst"), _kv(v_dst, shape, "v_dst")
+    new_len = ctypes.c_int32(-1)
+    _check(lib().scalekv_step_static(ctypes.byref(cs), _ptr(q), _ptr(k_cur), _ptr(v_cur), int(n_cur), win,
+                                     int(len(win_idx)), ctypes.byref(a), ctypes.byref(b), int(cache_len),
+                                     int(budget), ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len),
+                                     _ptr(out), _ptr(idx_out), _stream()))
+    if idx_out is not None and idx_out.shape[2] != new_len.value - n_cur:
+        raise ScaleKVError(1, f"idx_out holds {idx_out.shape[2]} entries per unit, the step kept {new_len.value - n_cur}")
     return int(new_len.value)
 
 

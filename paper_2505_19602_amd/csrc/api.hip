@@ -314,12 +314,46 @@ scalekv_status scalekv_attend(const scalekv_shape* shape, const void* q, int32_t
   return SCALEKV_OK;
 }
 
-scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const void* k_cur,
-                            const void* v_cur, int32_t n_cur, const int32_t* win_idx,
-                            int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
-                            int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
-                            const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
-                            int32_t* idx_out, void* ws, size_t ws_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Library-owned scratch of scalekv_step_static: one array per GPU (every device that loads
+// this code holds its own copy, at its own address, until the process ends).  Host code must
+// never pass the array's name to a kernel: the name is a host-side stand-in, the device
+// address comes from hipGetSymbolAddress, once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[SCALEKV_STATIC_SCRATCH_BYTES];
+constexpr int kMaxScratchDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxScratchDevices];
+
+// Device address of the current device's scratch array.  Racing first calls all resolve the
+// same address; nothing is allocated here.
+scalekv_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxScratchDevices)
+    return fail(SCALEKV_ERR_UNSUPPORTED, "device ordinal %d is outside 0..%d", dev,
+                kMaxScratchDevices - 1);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(SCALEKV_ERR_HIP, "hipGetSymbolAddress(scratch) returned a NULL address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return SCALEKV_OK;
+}
+
+// The step behind scalekv_step and scalekv_step_static.  `static_ws`: take the workspace from
+// the library's scratch array (ws / ws_bytes ignored) instead of from the caller.
+scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* k_cur,
+                         const void* v_cur, int32_t n_cur, const int32_t* win_idx, int32_t n_win,
+                         const scalekv_kv* k_src, const scalekv_kv* v_src, int32_t cache_len,
+                         int32_t budget, const scalekv_kv* k_dst, const scalekv_kv* v_dst,
+                         int32_t* new_len_out, void* out, int32_t* idx_out, void* ws,
+                         size_t ws_bytes, bool static_ws, void* stream) {
   SCALEKV_TRY(check_shape(shape));
   if (n_cur < 1) return fail(SCALEKV_ERR_INVALID_ARG, "n_cur must be >= 1 (got %d)", n_cur);
   SCALEKV_TRY(check_rows(shape, n_cur, "n_cur"));
@@ -337,7 +371,16 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
       if (win_idx[j] < 0 || win_idx[j] >= n_cur)
         return fail(SCALEKV_ERR_INVALID_ARG, "win_idx[%d] = %d is outside 0..n_cur-1", j,
                     win_idx[j]);
-    SCALEKV_TRY(check_ws(shape, cache_len, ws, ws_bytes));
+    if (static_ws) {
+      const size_t need = ws_layout(shape, cache_len).total;
+      if (need > (size_t)SCALEKV_STATIC_SCRATCH_BYTES)
+        return fail(SCALEKV_ERR_WORKSPACE,
+                    "this shape needs %zu bytes of scratch, the library's static array holds %zu "
+                    "(n_seq * n_head * cache_len too large for scalekv_step_static)",
+                    need, (size_t)SCALEKV_STATIC_SCRATCH_BYTES);
+    } else {
+      SCALEKV_TRY(check_ws(shape, cache_len, ws, ws_bytes));
+    }
   }
   SCALEKV_TRY(check_rows(shape, (long long)keep + n_cur, "keep + n_cur"));
   SCALEKV_TRY(check_dense(q, true, "q"));
@@ -358,6 +401,7 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
         dense_overlaps(shape, v_cur, n_cur, c) || dense_overlaps(shape, out, n_cur, c))
       return fail(SCALEKV_ERR_INVALID_ARG, "q, k_cur, v_cur or out overlaps a destination cache");
 
+  if (static_ws && ranks) SCALEKV_TRY(static_scratch(&ws));  // every argument check has passed
   hipStream_t st = static_cast<hipStream_t>(stream);
   void** ev = g_stage_events;
   auto mark = [&](int i) -> hipError_t {
@@ -422,6 +466,30 @@ scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const voi
   }
   if (new_len_out) *new_len_out = keep + n_cur;
   return SCALEKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+scalekv_status scalekv_step(const scalekv_shape* shape, const void* q, const void* k_cur,
+                            const void* v_cur, int32_t n_cur, const int32_t* win_idx,
+                            int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
+                            int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
+                            const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
+                            int32_t* idx_out, void* ws, size_t ws_bytes, void* stream) {
+  return step_impl(shape, q, k_cur, v_cur, n_cur, win_idx, n_win, k_src, v_src, cache_len, budget,
+                   k_dst, v_dst, new_len_out, out, idx_out, ws, ws_bytes, false, stream);
+}
+
+scalekv_status scalekv_step_static(const scalekv_shape* shape, const void* q, const void* k_cur,
+                                   const void* v_cur, int32_t n_cur, const int32_t* win_idx,
+                                   int32_t n_win, const scalekv_kv* k_src, const scalekv_kv* v_src,
+                                   int32_t cache_len, int32_t budget, const scalekv_kv* k_dst,
+                                   const scalekv_kv* v_dst, int32_t* new_len_out, void* out,
+                                   int32_t* idx_out, void* stream) {
+  return step_impl(shape, q, k_cur, v_cur, n_cur, win_idx, n_win, k_src, v_src, cache_len, budget,
+                   k_dst, v_dst, new_len_out, out, idx_out, nullptr, 0, true, stream);
 }
 
 scalekv_status scalekv_window_centroids(int32_t map_h, int32_t map_w, int32_t patch_rows,

@@ -145,6 +145,32 @@ def test_attend_and_step_argument_errors(L):
     assert step(n_cur=60, budget=10) == 1 and "capacity" in _err(L)   # keep + n_cur > dst capacity
 
 
+def test_step_static_checks_arguments_and_its_size_limit_before_touching_a_device(L):
+    s = _shape()
+    p = ctypes.c_void_p
+    gib = 1 << 30
+    cap = 600000                                     # 2 units x 600000 rows need ~86 MB of scratch
+    k, v, kd, vd = (_kv((4 + i) * gib, cap=cap + 64) for i in range(4))
+    win = (ctypes.c_int32 * 4)(0, 1, 2, 3)
+    new_len = ctypes.c_int32(-1)
+
+    def step(n_cur=8, n_win=4, cache_len=40, budget=10):
+        return L.scalekv_step_static(ctypes.byref(s), p(0x1000), p(0x2000), p(0x3000), n_cur, win, n_win,
+                                     ctypes.byref(k), ctypes.byref(v), cache_len, budget, ctypes.byref(kd),
+                                     ctypes.byref(vd), ctypes.byref(new_len), p(0x4000), p(0), None)
+    need = ctypes.c_size_t(0)
+    assert L.scalekv_workspace_bytes(ctypes.byref(s), cap, 8, ctypes.byref(need)) == 0
+    assert need.value > skv.STATIC_SCRATCH_BYTES
+    assert step(cache_len=cap, budget=100) == 3 and "static" in _err(L)      # beyond the array: refused, nothing launched
+    assert step(n_cur=0) == 1
+    assert step(n_win=17, n_cur=32) == 1
+    assert step(budget=-2) == 1
+    assert step(n_win=4, n_cur=3) == 1               # window larger than the map
+    header = open(os.path.join(ROOT, "include", "scalekv.h")).read()
+    m = re.search(r"#define SCALEKV_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == skv.STATIC_SCRATCH_BYTES
+
+
 def test_binding_rejects_wrong_tensors_before_calling_c():
     shape = skv.Shape(1, 2, 128, torch.bfloat16)
     q = torch.zeros(1, 2, 4, 128, dtype=torch.bfloat16)
