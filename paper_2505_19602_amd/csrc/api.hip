@@ -418,21 +418,32 @@ scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* 
                               : reinterpret_cast<int32_t*>(static_cast<char*>(ws) + w.idx_off);
     WindowRows rows;
     for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
-    SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
-                                    (long long)n_cur * shape->head_dim, rows, n_win, view(k_src),
-                                    cache_len, resolve_scale(shape), sw, st),
-                "score logits launch");
-    SCALEKV_HIP(mark(1), "event record");
-    // the finalisation of the score is fused into the select; very long caches take the
-    // two-kernel route through the scores buffer
-    hipError_t fused = launch_select_from_logits(U, n_win, sw, cache_len, keep, idx_ws, nullptr, st);
-    if (fused == hipErrorNotSupported) {
-      SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
-                  "score finalize launch");
-      SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, nullptr, st),
-                  "select launch");
+    // One launch for the whole ranking where it pays (enough units to fill the chip, or short
+    // caches): the selection kernel streams the keys itself.  Then event 1 coincides with event 0.
+    hipError_t one = launch_score_select(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
+                                         (long long)n_cur * shape->head_dim, rows, n_win,
+                                         view(k_src), cache_len, resolve_scale(shape), sw, keep,
+                                         idx_ws, nullptr, st);
+    if (one == hipErrorNotSupported) {
+      SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
+                                      (long long)n_cur * shape->head_dim, rows, n_win, view(k_src),
+                                      cache_len, resolve_scale(shape), sw, st),
+                  "score logits launch");
+      SCALEKV_HIP(mark(1), "event record");
+      // the finalisation of the score is fused into the select; very long caches take the
+      // three-kernel route through the scores buffer
+      hipError_t fused = launch_select_from_logits(U, n_win, sw, cache_len, keep, idx_ws, nullptr, st);
+      if (fused == hipErrorNotSupported) {
+        SCALEKV_HIP(launch_score_finalize(U, n_win, cache_len, sw, scores, w.len_pad, st),
+                    "score finalize launch");
+        SCALEKV_HIP(launch_select(U, scores, w.len_pad, cache_len, keep, idx_ws, nullptr, st),
+                    "select launch");
+      } else {
+        SCALEKV_HIP(fused, "fused select launch");
+      }
     } else {
-      SCALEKV_HIP(fused, "fused select launch");
+      SCALEKV_HIP(one, "score + select launch");
+      SCALEKV_HIP(mark(1), "event record");   // after the launch: the stage pair (score, select) shares it
     }
     idx = idx_ws;
   } else {
@@ -653,17 +664,24 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
     float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + w.scores_off);
     WindowRows rows;
     for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
-    SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, d, q,
-                                    (long long)n_cur * d, rows, n_win, view(k_cache), len,
-                                    resolve_scale(shape), sw, st),
-                "score logits launch");
-    hipError_t fused = launch_select_from_logits(U, n_win, sw, len, keep, idx_ws, &ex, st);
-    if (fused == hipErrorNotSupported) {
-      SCALEKV_HIP(launch_score_finalize(U, n_win, len, sw, scores, w.len_pad, st),
-                  "score finalize launch");
-      SCALEKV_HIP(launch_select(U, scores, w.len_pad, len, keep, idx_ws, &ex, st), "select launch");
+    hipError_t one = launch_score_select(shape->dtype, shape->n_seq, shape->n_head, d, q, (long long)n_cur * d, rows,
+                                         n_win, view(k_cache), len, resolve_scale(shape), sw, keep,
+                                         idx_ws, &ex, st);
+    if (one == hipErrorNotSupported) {
+      SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, d, q,
+                                      (long long)n_cur * d, rows, n_win, view(k_cache), len,
+                                      resolve_scale(shape), sw, st),
+                  "score logits launch");
+      hipError_t fused = launch_select_from_logits(U, n_win, sw, len, keep, idx_ws, &ex, st);
+      if (fused == hipErrorNotSupported) {
+        SCALEKV_HIP(launch_score_finalize(U, n_win, len, sw, scores, w.len_pad, st),
+                    "score finalize launch");
+        SCALEKV_HIP(launch_select(U, scores, w.len_pad, len, keep, idx_ws, &ex, st), "select launch");
+      } else {
+        SCALEKV_HIP(fused, "fused select launch");
+      }
     } else {
-      SCALEKV_HIP(fused, "fused select launch");
+      SCALEKV_HIP(one, "score + select launch");
     }
   }
   SCALEKV_HIP(mark(3), "event record");

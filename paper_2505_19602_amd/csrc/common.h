@@ -72,6 +72,18 @@ hipError_t launch_select(int n_unit, const float* scores, long long score_unit_s
 hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, int cache_len,
                                      int keep, int32_t* idx, const SelectExtras* extras,
                                      hipStream_t stream);
+// The whole ranking step in one launch (bf16 only): one workgroup per unit forms the logits of
+// the window rows against the unit's cached keys, the row normalisers and the log-scores
+// (Eq. 5) and selects.  Worth it when there are enough units to fill the chip or the caches are
+// short; returns hipErrorNotSupported otherwise (and for fp32 or very long caches), and the
+// caller takes the two launches.  The logits part of `ws` is used, the chunk statistics are not.
+inline bool score_select_fits(int dtype, int d, int n_unit, int cache_len) {
+  return dtype == 1 && (d == 64 || d == 128) && cache_len <= 12288 && (n_unit >= 64 || cache_len <= 4096);
+}
+hipError_t launch_score_select(int dtype, int n_seq, int n_head, int d, const void* q, long long q_unit_stride,
+                               WindowRows rows, int n_win, KvView k, int cache_len, float sm_scale,
+                               ScoreWorkspace ws, int keep, int32_t* idx, const SelectExtras* extras,
+                               hipStream_t stream);
 // first n_sink and last keep - n_sink positions of every unit (n_sink <= keep <= cache_len)
 hipError_t launch_positional(int n_unit, int cache_len, int n_sink, int keep, int32_t* idx,
                              hipStream_t stream);

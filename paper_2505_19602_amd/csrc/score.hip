@@ -9,6 +9,7 @@
 // into the row normalisers and folds the rows with a log-sum-exp, so no
 // probability is ever rounded below fp32 and nothing underflows.
 #include "common.h"
+#include "score_mfma.h"
 
 namespace scalekv {
 namespace {
@@ -94,77 +95,26 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
   }
 }
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-// bf16 logits kernel: the HBM-bound part of the score.  Each wave multiplies 64 keys
-// by the 16 window queries with MFMA 16x16x32 (A = key rows read straight from global
-// memory, 16 bytes per lane, every byte of every key row exactly once; B = window
-// queries in registers).  All of a wave's key vectors are requested before the first
-// MFMA so that 16 KB per wave are in flight.
-//   A (16 x 32): lane holds row l%16, k-indices 8(l/16)..+7
-//   B (32 x 16): lane holds column l%16, k-indices 8(l/16)..+7
-//   C (16 x 16): lane holds column l%16, rows 4(l/16) + v, v = 0..3
+// bf16 logits kernel: the HBM-bound part of the score.  Each wave handles 64 keys of the
+// workgroup's 256-key chunk (see score_mfma.h) and the workgroup leaves the chunk's row maximum
+// and sum of exponentials for the finalisation.
 template <int D>
 __global__ __launch_bounds__(kThreads) void score_logits_mfma_kernel(
     const uint16_t* __restrict__ q, long long q_unit_stride, WindowRows rows, int n_win,
     const uint16_t* __restrict__ k, long long k_seq_stride, long long k_head_stride, int n_head,
     int cache_len, float sm_scale, ScoreWorkspace ws) {
-  constexpr int NSL = D / 32;  // k-slabs
-  constexpr int NT = 4;        // 16-key tiles per wave
+  constexpr int NT = 4;  // 16-key tiles per wave
   __shared__ float red_max[kThreads / 64][kMaxWindow];
   __shared__ float red_sum[kThreads / 64][kMaxWindow];
   const int unit = blockIdx.y;
   const int seq = unit / n_head, head = unit - seq * n_head;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int i = lane & 15, g = lane >> 4;
-  const uint16_t* qu = q + unit * q_unit_stride;
   const uint16_t* ku = k + seq * k_seq_stride + head * k_head_stride;
-
-  bf16x8 qf[NSL];
-#pragma unroll
-  for (int sl = 0; sl < NSL; ++sl) {
-    uint4 raw = make_uint4(0, 0, 0, 0);
-    if (i < n_win) raw = *(const uint4*)(qu + (long long)rows.row[i] * D + 32 * sl + 8 * g);
-    qf[sl] = __builtin_bit_cast(bf16x8, raw);
-  }
-  const int key0 = blockIdx.x * kScoreChunk + wave * (16 * NT);
-  bf16x8 kf[NT][NSL];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int key = min(key0 + 16 * t + i, cache_len - 1);  // clamp: legal address, value unused
-#pragma unroll
-    for (int sl = 0; sl < NSL; ++sl)
-      kf[t][sl] = __builtin_bit_cast(bf16x8, *(const uint4*)(ku + (long long)key * D + 32 * sl + 8 * g));
-  }
-  float m = -INFINITY;
-  f32x4 c[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    c[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int sl = 0; sl < NSL; ++sl)
-      c[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][sl], qf[sl], c[t], 0, 0, 0);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int key = key0 + 16 * t + 4 * g + v;
-      c[t][v] = key < cache_len ? c[t][v] * sm_scale : -INFINITY;
-      m = fmaxf(m, c[t][v]);
-      if (key < cache_len) ws.logits[((long long)unit * ws.len_pad + key) * kMaxWindow + i] = c[t][v];
-    }
-  }
-  // row statistics of window row i over this wave's 64 keys, then over the workgroup
-  m = fmaxf(m, __shfl_xor(m, 16));
-  m = fmaxf(m, __shfl_xor(m, 32));
-  float e = 0.f;
-  if (m > -INFINITY) {
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) e += expf(c[t][v] - m);
-  }
-  e += __shfl_xor(e, 16);
-  e += __shfl_xor(e, 32);
+  score_bf16x8 qf[D / 32];
+  score_load_window<D>(q + unit * q_unit_stride, rows, n_win, qf);
+  float m, e;
+  score_wave_logits<D, NT>(ku, qf, blockIdx.x * kScoreChunk + wave * (16 * NT), cache_len, sm_scale,
+                           ws.logits + (long long)unit * ws.len_pad * kMaxWindow, m, e);
   if (lane < kMaxWindow) { red_max[wave][lane] = m; red_sum[wave][lane] = e; }
   __syncthreads();
   if (tid < kMaxWindow) {

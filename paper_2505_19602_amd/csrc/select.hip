@@ -13,6 +13,7 @@
 // largest key, and `keep` counts them.
 #include "common.h"
 #include "radix_select.h"
+#include "score_mfma.h"
 
 namespace scalekv {
 namespace {
@@ -20,6 +21,7 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kLdsKeys = 12288;  // units up to this many scores keep their keys in LDS
+static_assert(kLdsKeys == 12288, "score_select_fits() in common.h states the same limit");
 
 // FUSED: the scores are not read but formed here from the logits workspace (the score
 // finalisation), so the fused step neither writes nor re-reads them.
@@ -35,19 +37,36 @@ __device__ __forceinline__ float pooled_log(Load v, int i, int len, int r) {
   return m + logf(acc) - logf((float)(2 * r + 1));
 }
 
-template <bool IN_LDS, bool FUSED>
+// What the kernel needs to form the logits itself (SCORE_D != 0): bf16 storage only.
+struct ScoreInputs {
+  const uint16_t* q;        // [U, *, D]; window queries are rows `rows` of every unit
+  long long q_unit_stride;
+  WindowRows rows;
+  const uint16_t* k;        // cache
+  long long k_seq_stride, k_head_stride;
+  int n_head;
+  float sm_scale;
+};
+
+// SCORE_D = 64 / 128: the whole ranking step of Sec. 3.3 in one kernel.  The workgroup first
+// streams the unit's cached keys itself (16 waves x 32 keys per round, logits to the workspace,
+// running row maximum and sum of exponentials per wave), so that neither a second launch nor the
+// per-chunk statistics are needed; then it ranks as in the FUSED form.
+template <bool IN_LDS, bool FUSED, int SCORE_D>
 __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
                                                           long long score_unit_stride,
                                                           int cache_len, int keep,
                                                           int32_t* __restrict__ idx,
                                                           ScoreWorkspace ws, int n_win,
-                                                          SelectExtras ex) {
+                                                          SelectExtras ex, ScoreInputs si) {
   static_assert(IN_LDS || !FUSED, "the fused form keeps its keys in LDS");
+  static_assert(FUSED || SCORE_D == 0, "forming the logits here implies the fused form");
   constexpr int kPerThread = IN_LDS ? kLdsKeys / kThreads : 1;
   __shared__ uint32_t keys[IN_LDS ? kLdsKeys : 1];
   __shared__ float row_shift[kMaxWindow];
   __shared__ __attribute__((aligned(16))) uint32_t hist[kRadixHistWords];
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
+  __shared__ float red_max[SCORE_D ? kWaves : 1][kMaxWindow], red_sum[SCORE_D ? kWaves : 1][kMaxWindow];
 
   const int unit = blockIdx.x;
   const int tid = threadIdx.x;
@@ -66,7 +85,35 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   if constexpr (IN_LDS) {
     // log-scores into LDS (formed from the logits workspace when FUSED), pooled in place if
     // asked for, then turned into keys
-    if constexpr (FUSED) {
+    if constexpr (SCORE_D != 0) {
+      // Eq. 5, logits and row normalisers: every wave walks its share of the keys, 32 per round
+      constexpr int NT = 2;
+      const int lane = tid & 63, wave = tid >> 6;
+      const int seq = unit / si.n_head, head = unit - seq * si.n_head;
+      const uint16_t* ku = si.k + seq * si.k_seq_stride + head * si.k_head_stride;
+      float* logits_unit = ws.logits + (long long)unit * ws.len_pad * kMaxWindow;
+      score_bf16x8 qf[SCORE_D / 32];
+      score_load_window<SCORE_D>(si.q + unit * si.q_unit_stride, si.rows, n_win, qf);
+      float m_run = -INFINITY, e_run = 0.f;
+      for (int key0 = wave * (16 * NT); key0 < cache_len; key0 += kWaves * 16 * NT) {
+        float m, e;
+        score_wave_logits<SCORE_D, NT>(ku, qf, key0, cache_len, si.sm_scale, logits_unit, m, e);
+        const float m_new = fmaxf(m_run, m);   // m is finite: the round has at least one valid key
+        e_run = e_run * expf(m_run - m_new) + e * expf(m - m_new);
+        m_run = m_new;
+      }
+      if (lane < kMaxWindow) { red_max[wave][lane] = m_run; red_sum[wave][lane] = e_run; }
+      __syncthreads();   // also makes the logits visible to the whole workgroup
+      if (tid < kMaxWindow) {
+        float mm = -INFINITY;
+        for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, red_max[w][tid]);
+        float z = 0.f;
+        for (int w = 0; w < kWaves; ++w)
+          if (red_max[w][tid] > -INFINITY) z += red_sum[w][tid] * expf(red_max[w][tid] - mm);
+        row_shift[tid] = tid < n_win ? mm + logf(z) : 0.f;
+      }
+      __syncthreads();
+    } else if constexpr (FUSED) {
       if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
       __syncthreads();
     }
@@ -171,12 +218,13 @@ hipError_t launch_select(int n_unit, const float* scores, long long score_unit_s
     return hipGetLastError();
   }
   const ScoreWorkspace none{nullptr, nullptr, 0, 0};
+  const ScoreInputs no_score{};
   if (cache_len <= kLdsKeys)
-    hipLaunchKernelGGL((select_kernel<true, false>), dim3(n_unit), dim3(kThreads), 0, stream,
-                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex);
+    hipLaunchKernelGGL((select_kernel<true, false, 0>), dim3(n_unit), dim3(kThreads), 0, stream,
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex, no_score);
   else
-    hipLaunchKernelGGL((select_kernel<false, false>), dim3(n_unit), dim3(kThreads), 0, stream,
-                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex);
+    hipLaunchKernelGGL((select_kernel<false, false, 0>), dim3(n_unit), dim3(kThreads), 0, stream,
+                       scores, score_unit_stride, cache_len, keep, idx, none, 0, ex, no_score);
   return hipGetLastError();
 }
 
@@ -188,8 +236,29 @@ hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, i
   if (extras) ex = *extras;
   if (cache_len > kLdsKeys) return hipErrorNotSupported;
   if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
-  hipLaunchKernelGGL((select_kernel<true, true>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
-                     0, cache_len, keep, idx, ws, n_win, ex);
+  hipLaunchKernelGGL((select_kernel<true, true, 0>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
+                     0, cache_len, keep, idx, ws, n_win, ex, ScoreInputs{});
+  return hipGetLastError();
+}
+
+hipError_t launch_score_select(int dtype, int n_seq, int n_head, int d, const void* q, long long q_unit_stride,
+                               WindowRows rows, int n_win, KvView k, int cache_len, float sm_scale,
+                               ScoreWorkspace ws, int keep, int32_t* idx, const SelectExtras* extras,
+                               hipStream_t stream) {
+  SelectExtras ex{};
+  ex.pool_w = 1;
+  if (extras) ex = *extras;
+  const int n_unit = n_seq * n_head;
+  if (!score_select_fits(dtype, d, n_unit, cache_len)) return hipErrorNotSupported;
+  if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
+  const ScoreInputs si{(const uint16_t*)q, q_unit_stride, rows, (const uint16_t*)k.ptr, k.seq_stride,
+                       k.head_stride, n_head, sm_scale};
+  if (d == 128)
+    hipLaunchKernelGGL((select_kernel<true, true, 128>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
+                       0, cache_len, keep, idx, ws, n_win, ex, si);
+  else
+    hipLaunchKernelGGL((select_kernel<true, true, 64>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
+                       0, cache_len, keep, idx, ws, n_win, ex, si);
   return hipGetLastError();
 }
 
