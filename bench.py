@@ -23,6 +23,11 @@ workload.
   sinks     the same with the first 16 positions kept as well
 The last three are the comparison policies of Sec. 4.1 at the same total budget: their cost,
 not their quality.
+
+--cases L,B,N[;L,B,N...] runs nothing but a few scalekv_step calls of the listed shapes
+(cache_len, budget, n_cur) on random inputs after a 1 GiB device-to-device copy, for use under
+rocprofv3: the copy calibrates the hardware byte counters (FETCH_SIZE, WRITE_SIZE), and the n-th
+group of the library's kernels in the trace belongs to the n-th case.
 """
 from __future__ import annotations
 
@@ -58,6 +63,8 @@ ATTEND_PIPE_TRAFFIC = {
 
 VARIANTS = ("scalekv", "literal", "pyramid", "sliding", "sinks", "calibrated")
 # stages between consecutive events of one call, per variant
+# ("score" holds the whole ranking where the selection kernel streams the keys itself: one launch;
+# "select" is then only what lies between two events)
 STAGES = {
     "scalekv": ("score", "select", "compact", "attend"),
     "pyramid": ("score", "select", "compact", "attend"),
@@ -211,6 +218,97 @@ def final_scale_sweep(args, torch, skv, W, cfg) -> int:
     return 0
 
 
+def run_cases(args, torch, skv) -> int:
+    """--cases: a calibration copy, then `--reps` scalekv_step calls per listed shape."""
+    dev, dt = "cuda", torch.bfloat16
+    S, H, d = args.case_seqs, args.case_heads, 128
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(args.reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+    shape = skv.Shape(S, H, d, dt)
+    g = torch.Generator(device=dev).manual_seed(0)
+    rnd = lambda rows: torch.randn(S, H, rows, d, device=dev, dtype=torch.float32, generator=g).to(dt)
+    for case in args.cases.split(";"):
+        L, budget, n = (int(x) for x in case.split(","))
+        q, kc, vc, ks, vs = rnd(n), rnd(n), rnd(n), rnd(L), rnd(L)
+        keep = min(budget, L)
+        kd = torch.empty(S, H, keep + n, d, device=dev, dtype=dt)
+        vd = torch.empty_like(kd)
+        out = torch.empty_like(q)
+        ws = torch.empty(skv.workspace_bytes(shape, L, n), dtype=torch.uint8, device=dev)
+        win = list(range(max(0, n - 16), n))
+        for _ in range(args.reps):
+            skv.step(shape, q, kc, vc, win, ks, vs, L, budget, kd, vd, out, None, ws)
+        torch.cuda.synchronize()
+        print(f"ran {args.reps} steps: cache_len={L} keep={keep} n_cur={n} units={S * H}", flush=True)
+        del q, kc, vc, ks, vs, kd, vd, out, ws
+    return 0
+
+
+def parity_replay(torch, skv, W, cfg, shape, inputs, prefix, bufs, table, lens_before_last, windows, ws,
+                  n_units: int = 2, n_rows: int = 48):
+    """After the timed region: the last scale's call of one drafter layer and one refiner layer is
+    issued once more with the very arguments the timed passes used (same shapes, same launch
+    configuration, same source cache, which the passes leave intact), now also returning its
+    indices, and sampled units are replayed through the fp64 oracle: indices by the margin rule,
+    the new cache bit for bit, the attention output on sampled query rows."""
+    import numpy as np
+    import oracle
+    K, S, H, d = cfg.n_scale, cfg.n_seq, cfg.n_head, cfg.head_dim
+    U = S * H
+    n_cur = cfg.n_tokens(K)
+    roles = W.layer_roles(cfg, K)
+    layers = sorted({roles.index(True), roles.index(False)}) if (True in roles and False in roles) else [0]
+    units = [int(u) for u in np.linspace(0, U - 1, n_units).round()]
+    rows = sorted({int(r) for r in np.linspace(0, n_cur - 1, n_rows).round()})
+    stats = dict(layers=layers, units=units, query_rows=len(rows), exact=0, band=0, kv_bit_exact=True, max_err=0.0,
+                 mean_err=0.0, tolerance="indices: equal where the keep-th / (keep+1)-th score margin exceeds 1e-4, "
+                 "else inside the band; K'/V' bit-exact; output 2e-2 max-abs, 1e-2 mean-abs (bf16)")
+    flat = lambda t: t.reshape(U, t.shape[2], d)
+    errs = []
+    for l in layers:
+        x = inputs[(l, K)]
+        src = bufs[l][(K - 1) % 2] if K > 1 else prefix[l]
+        dst = bufs[l][K % 2]
+        L, budget = lens_before_last[l], table[l][K - 1]
+        keep = min(budget, L)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=x.q.device)
+        out = torch.empty_like(x.q)
+        new_len = skv.step(shape, x.q, x.k_cur, x.v_cur, windows[K], src[0], src[1], L, budget, dst[0], dst[1], out, idx, ws)
+        torch.cuda.synchronize()
+        g_idx = idx.cpu().numpy().reshape(U, keep)[units]
+        q_u, kc_u, vc_u = (flat(t)[units].cpu() for t in (x.q, x.k_cur, x.v_cur))
+        ks_u, vs_u = (flat(t[:, :, :L])[units].cpu() for t in src)
+        if 0 < keep < L:
+            _, ls = oracle.score(q_u[:, windows[K]], ks_u)
+            own = oracle.select(ls, budget)
+            for i in range(len(units)):
+                order = np.sort(ls[i])[::-1]
+                la, lb = order[keep - 1], order[keep]
+                if lb - la < np.log1p(-1e-4):
+                    assert np.array_equal(g_idx[i], own[i]), f"parity: indices differ at a wide margin (layer {l}, unit {units[i]})"
+                    stats["exact"] += 1
+                else:
+                    chosen = np.zeros(L, dtype=bool); chosen[g_idx[i]] = True
+                    assert np.all(chosen[ls[i] > la + np.log1p(1e-4)]) and np.all(ls[i][chosen] >= la + np.log1p(-1e-4)), \
+                        f"parity: invalid choice inside the near-tie band (layer {l}, unit {units[i]})"
+                    stats["band"] += 1
+        k_new = oracle.compact(ks_u, g_idx, kc_u)
+        v_new = oracle.compact(vs_u, g_idx, vc_u)
+        got_k, got_v = (flat(t[:, :, :new_len])[units].cpu().double().numpy() for t in dst)
+        stats["kv_bit_exact"] = bool(stats["kv_bit_exact"] and np.array_equal(got_k, k_new) and np.array_equal(got_v, v_new))
+        ref = oracle.attend(q_u[:, rows], k_new, v_new)
+        got = flat(out)[units][:, rows].float().cpu().numpy().astype(np.float64)
+        errs.append(np.abs(got - ref))
+    err = np.concatenate([e.ravel() for e in errs])
+    stats["max_err"], stats["mean_err"] = float(err.max()), float(err.mean())
+    stats["ok"] = bool(stats["kv_bit_exact"] and stats["max_err"] <= 2e-2 and stats["mean_err"] <= 1e-2)
+    return stats
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -226,6 +324,13 @@ def main() -> int:
     ap.add_argument("--pool-w", type=int, default=7, help="score pooling width of --variant literal")
     ap.add_argument("--shared-inputs", action="store_true",
                     help="reuse layer 0's Q/K/V in every layer (less memory, faster set-up)")
+    ap.add_argument("--no-parity", action="store_true",
+                    help="skip the replay of sampled last-scale units through the CPU oracle after the timed region")
+    ap.add_argument("--cases", default=None,
+                    help="cache_len,budget,n_cur[;...]: only run these step shapes on random inputs (for rocprofv3)")
+    ap.add_argument("--reps", type=int, default=3, help="calls per shape of --cases")
+    ap.add_argument("--case-seqs", type=int, default=16)
+    ap.add_argument("--case-heads", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -239,6 +344,8 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     dev = "cuda"
+    if args.cases:
+        return run_cases(args, torch, skv)
     cfg = W.get_config(args.config)
     if cfg.name == "final_scale":
         return final_scale_sweep(args, torch, skv, W, cfg)
@@ -375,6 +482,7 @@ def main() -> int:
         return n_cur > 128 and dtype == torch.bfloat16 and d == 128
 
     calls, meta = [], []
+    lens_before_last = None
     lens = [cfg.prefix] * Lyr
     srcs = [prefix[l] for l in range(Lyr)]
     cur_buf = []
@@ -389,6 +497,8 @@ def main() -> int:
     for k in range(1, K + 1):
         n_cur = cfg.n_tokens(k)
         full = W.c_full(cfg, k)
+        if k == K:
+            lens_before_last = list(lens)
         for l in range(Lyr):
             x = inputs[(l, k)]
             dst = bufs[l][k % 2]
@@ -436,14 +546,15 @@ def main() -> int:
 
     lens_final = list(lens)
 
-    def run_sequence(ev_blocks=None):
-        """the whole multi-scale sequence: one call per (scale, layer)"""
-        if ev_blocks is None:
-            for call in calls:
-                call.run(None)
-        else:
-            for call, ev in zip(calls, ev_blocks):
-                call.run(ev)
+    def run_sequence(ev_blocks=None, scale_ev=None):
+        """the whole multi-scale sequence: one call per (scale, layer).  scale_ev: K + 1 events,
+        recorded on the launch stream before the first call of every scale and after the last call"""
+        for i, call in enumerate(calls):
+            if scale_ev is not None and i % Lyr == 0:
+                hip.hipEventRecord(scale_ev[i // Lyr], stream_ptr)
+            call.run(None if ev_blocks is None else ev_blocks[i])
+        if scale_ev is not None:
+            hip.hipEventRecord(scale_ev[K], stream_ptr)
 
     n_calls = Lyr * K
     for w in range(args.warmup):
@@ -463,16 +574,22 @@ def main() -> int:
             big_no[i] = len(big_no)
     ev_steps = [[events.block(n_ev, only=(att, att + 1)) if i in big_no and big_no[i] % args.steps == s else None
                  for i in range(len(meta))] for s in range(args.steps)]
+    # one event per scale boundary as well (14 per pass, about 60 us of stream time in all): the
+    # per-scale times of the timed passes themselves
+    scale_evs = [events.block(K + 1) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        run_sequence(ev_steps[s])
+        run_sequence(ev_steps[s], scale_evs[s])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     log(f"timed {args.steps} steps: {ms_per_step:.2f} ms per step")
 
+    per_scale_timed = {str(k): sum(events.elapsed_ms(scale_evs[s][k - 1], scale_evs[s][k]) for s in range(args.steps))
+                       / args.steps for k in range(1, K + 1)}
     attend_big = dict(ms=0.0, flops=0.0, launches=0, traffic=0.0, min_bytes=0.0)
+    attend_by_scale = {}
     traffic_known = (S, H, d) == (16, 16, 128)
     for s in range(args.steps):
         for i, m in enumerate(meta):
@@ -480,9 +597,12 @@ def main() -> int:
             if ev is None:
                 continue
             n_cur, kv_len = m["n_cur"], m["kv_len"]
-            attend_big["ms"] += events.elapsed_ms(ev[att], ev[att + 1])
+            t_ms = events.elapsed_ms(ev[att], ev[att + 1])
+            attend_big["ms"] += t_ms
             attend_big["flops"] += 4.0 * n_cur * kv_len * d * U
             attend_big["launches"] += 1
+            bs = attend_by_scale.setdefault(m["scale"], dict(ms=0.0, flops=0.0, launches=0))
+            bs["ms"] += t_ms; bs["flops"] += 4.0 * n_cur * kv_len * d * U; bs["launches"] += 1
             attend_big["min_bytes"] += (2.0 * n_cur + 2.0 * kv_len) * d * e * U + m["append_in_attend"]
             if traffic_known and (n_cur, kv_len - n_cur) in ATTEND_PIPE_TRAFFIC:
                 attend_big["traffic"] += ATTEND_PIPE_TRAFFIC[(n_cur, kv_len - n_cur)]
@@ -582,6 +702,11 @@ def main() -> int:
         "algorithmic_bytes_per_launch": dom["min_bytes"] / max(1, dom["launches"]),
         "launches": dom["launches"], "avg_launch_ms": dom["ms"] / max(1, dom["launches"]),
         "flops_per_launch_avg": dom["flops"] / max(1, dom["launches"]),
+        # the same per scale: every launch of the kernel at that scale, timed once inside the timed region
+        "per_scale": {str(k): {"launches": v["launches"], "ms": v["ms"],
+                               "achieved": v["flops"] / (v["ms"] * 1e-3) / 1e12 if v["ms"] > 0 else 0.0,
+                               "frac": v["flops"] / (v["ms"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if v["ms"] > 0 else 0.0}
+                      for k, v in sorted(attend_by_scale.items())},
     }
     gbs = lambda st: st["bytes"] / (st["ms"] * 1e-3) / 1e9 if st["ms"] > 0 else 0.0
     compact_gbs, score_gbs = gbs(compact_stat), gbs(score_stat)
@@ -599,6 +724,8 @@ def main() -> int:
                                f"{cfg.refiner_frac:.0%} per scale, window {cfg.window}",
                    "variant": variant, "calls_per_step": n_calls, "shared_inputs": bool(args.shared_inputs)},
         "roofline": roofline,
+        "per_scale_ms": per_scale_timed,
+        "parity": None,
         "stage_pass": None if ms_stage_pass is None else {
             "note": "one extra pass outside the timed region with an event at every stage boundary",
             "stages": list(stages),
@@ -659,6 +786,12 @@ def main() -> int:
                     "outside the timed region"}
         del a, b, src, dstb
         log(f"same box: bf16 GEMM {gemm_tflops:.0f} TFLOP/s, copy {copy_gbs:.0f} GB/s")
+    # ---- parity of what was just timed: sampled units of the last scale through the oracle
+    if not args.no_parity and variant == "scalekv":
+        log("replaying sampled last-scale units through the CPU oracle ...")
+        result["parity"] = parity_replay(torch, skv, W, cfg, shape, inputs, prefix, bufs, table, lens_before_last,
+                                         windows, ws)
+        log(f"parity: {result['parity']}")
     # ---- the same sequence captured once into a HIP graph and replayed (what a serving loop with
     # fixed shapes would do); reported beside the eager number, never in place of it.  Last GPU
     # work of the run, so that a failed capture cannot disturb any other measurement.

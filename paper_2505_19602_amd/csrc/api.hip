@@ -409,6 +409,8 @@ scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* 
   };
   const int U = shape->n_seq * shape->n_head;
   const int32_t* idx = nullptr;  // identity unless a ranking is needed
+  const bool pipe = attend_uses_pipe(shape->dtype, shape->head_dim, n_cur);
+  bool pruned = false;           // the ranking kernel has already written the destination caches
   SCALEKV_HIP(mark(0), "event record");
   if (ranks) {
     const WsLayout w = ws_layout(shape, cache_len);
@@ -420,10 +422,14 @@ scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* 
     for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
     // One launch for the whole ranking where it pays (enough units to fill the chip, or short
     // caches): the selection kernel streams the keys itself.  Then event 1 coincides with event 0.
+    // The same workgroup then prunes its unit as well: the kept rows go to the destination
+    // caches (and the map's rows behind them where the attention kernel does not append).
+    const PruneTarget prune{view(v_src), view(k_dst), view(v_dst), pipe ? nullptr : k_cur,
+                            pipe ? nullptr : v_cur, n_cur};
     hipError_t one = launch_score_select(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
                                          (long long)n_cur * shape->head_dim, rows, n_win,
                                          view(k_src), cache_len, resolve_scale(shape), sw, keep,
-                                         idx_ws, nullptr, st);
+                                         idx_ws, nullptr, &prune, st);
     if (one == hipErrorNotSupported) {
       SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim, q,
                                       (long long)n_cur * shape->head_dim, rows, n_win, view(k_src),
@@ -442,8 +448,9 @@ scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* 
         SCALEKV_HIP(fused, "fused select launch");
       }
     } else {
-      SCALEKV_HIP(one, "score + select launch");
-      SCALEKV_HIP(mark(1), "event record");   // after the launch: the stage pair (score, select) shares it
+      SCALEKV_HIP(one, "score + select + prune launch");
+      SCALEKV_HIP(mark(1), "event record");   // after the launch: the stages up to the pruning share it
+      pruned = true;
     }
     idx = idx_ws;
   } else {
@@ -455,12 +462,13 @@ scalekv_status step_impl(const scalekv_shape* shape, const void* q, const void* 
   SCALEKV_HIP(mark(2), "event record");
   // The pipelined attention kernel reads the map's own K/V from k_cur/v_cur and copies them
   // behind the kept rows itself (it is bound by the matrix pipe, the copy by the HBM, so the
-  // two overlap); for the other shapes the compaction kernel appends them.
-  const bool fused_append = attend_uses_pipe(shape->dtype, shape->head_dim, n_cur);
-  SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
-                             view(k_src), view(v_src), idx, keep, k_cur, v_cur,
-                             fused_append ? 0 : n_cur, view(k_dst), view(v_dst), st),
-              "compact launch");
+  // two overlap); for the other shapes the pruning appends them.
+  const bool fused_append = pipe;
+  if (!pruned)
+    SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, shape->head_dim,
+                               view(k_src), view(v_src), idx, keep, k_cur, v_cur,
+                               fused_append ? 0 : n_cur, view(k_dst), view(v_dst), st),
+                "compact launch");
   if (fused_append) {
     // events 3 and 4 ride on this kernel's dispatch: its own start and end
     SCALEKV_HIP(launch_attend_pipe(U, shape->n_head, q, n_cur, view(k_dst), view(v_dst), keep, k_cur,
@@ -655,6 +663,7 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
     return SCALEKV_OK;
   }
   // 3. scores of the window rows against the whole cache, pooled; window kept + top-budget
+  bool pruned = false;  // the ranking kernel has already written the next cache
   int32_t* idx_ws = idx_out;
   if (!idx_ws && ranks)
     idx_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + ws_layout(shape, len).idx_off);
@@ -664,9 +673,11 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
     float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + w.scores_off);
     WindowRows rows;
     for (int j = 0; j < kMaxWindow; ++j) rows.row[j] = j < n_win ? win_idx[j] : 0;
+    // (the ranking workgroup also moves its unit's kept rows into the next cache)
+    const PruneTarget prune{view(v_cache), view(k_next), view(v_next), nullptr, nullptr, 0};
     hipError_t one = launch_score_select(shape->dtype, shape->n_seq, shape->n_head, d, q, (long long)n_cur * d, rows,
                                          n_win, view(k_cache), len, resolve_scale(shape), sw, keep,
-                                         idx_ws, &ex, st);
+                                         idx_ws, &ex, &prune, st);
     if (one == hipErrorNotSupported) {
       SCALEKV_HIP(launch_score_logits(shape->dtype, shape->n_seq, shape->n_head, d, q,
                                       (long long)n_cur * d, rows, n_win, view(k_cache), len,
@@ -681,15 +692,17 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
         SCALEKV_HIP(fused, "fused select launch");
       }
     } else {
-      SCALEKV_HIP(one, "score + select launch");
+      SCALEKV_HIP(one, "score + select + prune launch");
+      pruned = true;
     }
   }
   SCALEKV_HIP(mark(3), "event record");
   // 4. the kept rows become the next cache
-  SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, d, view(k_cache),
-                             view(v_cache), idx_ws, keep, nullptr, nullptr, 0, view(k_next),
-                             view(v_next), st),
-              "compact launch");
+  if (!pruned)
+    SCALEKV_HIP(launch_compact(shape->dtype, shape->n_seq, shape->n_head, d, view(k_cache),
+                               view(v_cache), idx_ws, keep, nullptr, nullptr, 0, view(k_next),
+                               view(v_next), st),
+                "compact launch");
   SCALEKV_HIP(mark(4), "event record");
   return SCALEKV_OK;
 }

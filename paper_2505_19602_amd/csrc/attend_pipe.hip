@@ -412,6 +412,29 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   // every wave has left its last tile when the votes are in, so the stages may be refilled
   if (__syncthreads_or(overflowed != 0)) pass(std::true_type{});
 
+  // ---- append, first half: this workgroup's share of the second segment goes behind the first,
+  // as 16-byte vectors.  The vectors of the first round (the whole share when it is at most 128
+  // rows) are requested here, before the output is normalised and stored, so that their latency
+  // hides behind that work; the registers of the operand fragments are free by now.
+  const int ap_per = append ? (len2 + n_qtile - 1) / n_qtile : 0;
+  const int ap_row0 = min(qtile * ap_per, len2);
+  const int ap_vec = min(ap_per, len2 - ap_row0) * (kRowBytes / 16);  // per tensor
+  const u32x4* ap_ks = (const u32x4*)(k2u + (long long)ap_row0 * kRowBytes);
+  const u32x4* ap_vs = (const u32x4*)(v2u + (long long)ap_row0 * kRowBytes);
+  u32x4 ap_a[8], ap_b[8];
+  int ap_tid = tid;
+  asm volatile("" : "+v"(ap_tid));  // keeps the requests below the tile loop: they must not be hoisted into it
+  if (ap_vec > 0) {
+    // (lanes past the end of the share re-read its last vector and store nothing)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = min(u * 256 + ap_tid, ap_vec - 1);
+      ap_a[u] = ap_ks[i];
+      ap_b[u] = ap_vs[i];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
   // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
   {
     const int row = q_base + j;
@@ -432,32 +455,33 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
         }
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
 
-  // ---- append: this workgroup's share of the second segment goes behind the first, as 16-byte
-  // vectors.  Done last, when the accumulators are dead and a thread can hold its whole share
-  // (16 vectors when the share is 128 rows) in flight at once; the other workgroup on the
-  // compute unit keeps the matrix pipe busy meanwhile.
-  if (append) {
-    const int per = (len2 + n_qtile - 1) / n_qtile;
-    const int row0 = min(qtile * per, len2);
-    const int n_vec = min(per, len2 - row0) * (kRowBytes / 16);  // per tensor
-    const u32x4* ks = (const u32x4*)(k2u + (long long)row0 * kRowBytes);
-    const u32x4* vs = (const u32x4*)(v2u + (long long)row0 * kRowBytes);
-    u32x4* kd = (u32x4*)(const_cast<unsigned char*>(ku) + (long long)(len1 + row0) * kRowBytes);
-    u32x4* vd = (u32x4*)(const_cast<unsigned char*>(vu) + (long long)(len1 + row0) * kRowBytes);
-    for (int i0 = 0; i0 < n_vec; i0 += 8 * 256) {
-      u32x4 a[8], b[8];
+  // ---- append, second half: store the first round, then whatever is left of a larger share.
+  // The other workgroup on the compute unit keeps the matrix pipe busy meanwhile.
+  if (ap_vec > 0) {
+    u32x4* kd = (u32x4*)(const_cast<unsigned char*>(ku) + (long long)(len1 + ap_row0) * kRowBytes);
+    u32x4* vd = (u32x4*)(const_cast<unsigned char*>(vu) + (long long)(len1 + ap_row0) * kRowBytes);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = u * 256 + tid;
+      if (i < ap_vec) {
+        __builtin_nontemporal_store(ap_a[u], kd + i);
+        __builtin_nontemporal_store(ap_b[u], vd + i);
+      }
+    }
+    for (int i0 = 8 * 256; i0 < ap_vec; i0 += 8 * 256) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int i = i0 + u * 256 + tid;
-        if (i < n_vec) { a[u] = ks[i]; b[u] = vs[i]; }
+        if (i < ap_vec) { ap_a[u] = ap_ks[i]; ap_b[u] = ap_vs[i]; }
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int i = i0 + u * 256 + tid;
-        if (i < n_vec) {
-          __builtin_nontemporal_store(a[u], kd + i);
-          __builtin_nontemporal_store(b[u], vd + i);
+        if (i < ap_vec) {
+          __builtin_nontemporal_store(ap_a[u], kd + i);
+          __builtin_nontemporal_store(ap_b[u], vd + i);
         }
       }
     }

@@ -80,10 +80,19 @@ hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, i
 inline bool score_select_fits(int dtype, int d, int n_unit, int cache_len) {
   return dtype == 1 && (d == 64 || d == 128) && cache_len <= 12288 && (n_unit >= 64 || cache_len <= 4096);
 }
+// With `prune` the same workgroup then also prunes its unit (Sec. 3.3): source row idx[t] of k
+// (keys) / prune->v_src (values) goes to row t of the destination caches, and the n_app rows of
+// k_cur / v_cur ([U, n_app, d], NULL: none) are appended behind the keep rows.
+struct PruneTarget {
+  KvView v_src, k_dst, v_dst;
+  const void* k_cur;
+  const void* v_cur;
+  int n_app;
+};
 hipError_t launch_score_select(int dtype, int n_seq, int n_head, int d, const void* q, long long q_unit_stride,
                                WindowRows rows, int n_win, KvView k, int cache_len, float sm_scale,
                                ScoreWorkspace ws, int keep, int32_t* idx, const SelectExtras* extras,
-                               hipStream_t stream);
+                               const PruneTarget* prune, hipStream_t stream);
 // first n_sink and last keep - n_sink positions of every unit (n_sink <= keep <= cache_len)
 hipError_t launch_positional(int n_unit, int cache_len, int n_sink, int keep, int32_t* idx,
                              hipStream_t stream);

@@ -46,6 +46,18 @@ struct ScoreInputs {
   long long k_seq_stride, k_head_stride;
   int n_head;
   float sm_scale;
+  // Pruning by the same workgroup (Sec. 3.3: the selected rows are preserved): after the
+  // selection, row idx[t] of the source caches is copied to row t of the destination caches, and
+  // n_app rows of k_cur / v_cur ([U, n_app, D]) are appended behind the kept ones.  Off if
+  // k_dst == NULL.  v_src may differ from the key cache in base and strides; strides in elements.
+  const uint16_t* v_src;
+  long long v_seq_stride, v_head_stride;
+  uint16_t* k_dst;
+  uint16_t* v_dst;
+  long long kd_seq_stride, kd_head_stride, vd_seq_stride, vd_head_stride;
+  const uint16_t* k_cur;
+  const uint16_t* v_cur;
+  int n_app;
 };
 
 // SCORE_D = 64 / 128: the whole ranking step of Sec. 3.3 in one kernel.  The workgroup first
@@ -175,6 +187,51 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
       ++eq_seen;
     }
   }
+
+  // ---- pruning: the kept rows (and, if asked, the map's rows behind them) into the destination
+  if constexpr (SCORE_D != 0) {
+    if (si.k_dst != nullptr) {
+      typedef unsigned int vec4 __attribute__((ext_vector_type(4)));
+      constexpr int VPR = SCORE_D * 2 / 16;  // 16-byte vectors per row
+      constexpr int kFly = 4;                // vectors in flight per thread and tensor
+      __syncthreads();  // the unit's index list is complete (written by this workgroup)
+      const int seq = unit / si.n_head, head = unit - seq * si.n_head;
+      const vec4* ksrc = (const vec4*)(si.k + seq * si.k_seq_stride + head * si.k_head_stride);
+      const vec4* vsrc = (const vec4*)(si.v_src + seq * si.v_seq_stride + head * si.v_head_stride);
+      vec4* kdst = (vec4*)(si.k_dst + seq * si.kd_seq_stride + head * si.kd_head_stride);
+      vec4* vdst = (vec4*)(si.v_dst + seq * si.vd_seq_stride + head * si.vd_head_stride);
+      const vec4* kcur = (const vec4*)(si.k_cur + (long long)unit * si.n_app * SCORE_D);
+      const vec4* vcur = (const vec4*)(si.v_cur + (long long)unit * si.n_app * SCORE_D);
+      const int total = (keep + si.n_app) * VPR;
+      for (int f0 = tid; f0 < total; f0 += kThreads * kFly) {
+        vec4 a[kFly], b[kFly];
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+          const int f = f0 + u * kThreads;
+          if (f < total) {
+            const int row = f / VPR, c = f % VPR;
+            if (row < keep) {
+              const long long o = (long long)out[row] * VPR + c;
+              a[u] = __builtin_nontemporal_load(ksrc + o);
+              b[u] = __builtin_nontemporal_load(vsrc + o);
+            } else {
+              const long long o = (long long)(row - keep) * VPR + c;
+              a[u] = __builtin_nontemporal_load(kcur + o);
+              b[u] = __builtin_nontemporal_load(vcur + o);
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+          const int f = f0 + u * kThreads;
+          if (f < total) {
+            __builtin_nontemporal_store(a[u], kdst + f);
+            __builtin_nontemporal_store(b[u], vdst + f);
+          }
+        }
+      }
+    }
+  }
 }
 
 __global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total) {
@@ -244,15 +301,26 @@ hipError_t launch_select_from_logits(int n_unit, int n_win, ScoreWorkspace ws, i
 hipError_t launch_score_select(int dtype, int n_seq, int n_head, int d, const void* q, long long q_unit_stride,
                                WindowRows rows, int n_win, KvView k, int cache_len, float sm_scale,
                                ScoreWorkspace ws, int keep, int32_t* idx, const SelectExtras* extras,
-                               hipStream_t stream) {
+                               const PruneTarget* prune, hipStream_t stream) {
   SelectExtras ex{};
   ex.pool_w = 1;
   if (extras) ex = *extras;
   const int n_unit = n_seq * n_head;
   if (!score_select_fits(dtype, d, n_unit, cache_len)) return hipErrorNotSupported;
   if (n_unit <= 0 || keep <= 0 || cache_len <= 0) return hipSuccess;
-  const ScoreInputs si{(const uint16_t*)q, q_unit_stride, rows, (const uint16_t*)k.ptr, k.seq_stride,
-                       k.head_stride, n_head, sm_scale};
+  ScoreInputs si{};
+  si.q = (const uint16_t*)q; si.q_unit_stride = q_unit_stride; si.rows = rows;
+  si.k = (const uint16_t*)k.ptr; si.k_seq_stride = k.seq_stride; si.k_head_stride = k.head_stride;
+  si.n_head = n_head; si.sm_scale = sm_scale;
+  if (prune) {
+    si.v_src = (const uint16_t*)prune->v_src.ptr;
+    si.v_seq_stride = prune->v_src.seq_stride; si.v_head_stride = prune->v_src.head_stride;
+    si.k_dst = (uint16_t*)const_cast<void*>(prune->k_dst.ptr); si.v_dst = (uint16_t*)const_cast<void*>(prune->v_dst.ptr);
+    si.kd_seq_stride = prune->k_dst.seq_stride; si.kd_head_stride = prune->k_dst.head_stride;
+    si.vd_seq_stride = prune->v_dst.seq_stride; si.vd_head_stride = prune->v_dst.head_stride;
+    si.k_cur = (const uint16_t*)prune->k_cur; si.v_cur = (const uint16_t*)prune->v_cur;
+    si.n_app = prune->k_cur ? prune->n_app : 0;
+  }
   if (d == 128)
     hipLaunchKernelGGL((select_kernel<true, true, 128>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
                        0, cache_len, keep, idx, ws, n_win, ex, si);

@@ -62,7 +62,13 @@ def _uniform16(key: int, start: int, count: int, device) -> torch.Tensor:
     last = (start + count + 3) // 4
     ctr = torch.arange(first, last, dtype=torch.int64, device=device)
     z = _hash64(key, ctr)
-    u = torch.stack([z & 0xFFFF, _lsr(z, 16) & 0xFFFF, _lsr(z, 32) & 0xFFFF, _lsr(z, 48) & 0xFFFF], dim=1)
+    # the four 16-bit lanes of every hash word, written into a tensor allocated beforehand (no
+    # concatenation kernel: element-wise writes only)
+    u = torch.empty(z.shape[0], 4, dtype=torch.int64, device=device)
+    u[:, 0] = z & 0xFFFF
+    u[:, 1] = _lsr(z, 16) & 0xFFFF
+    u[:, 2] = _lsr(z, 32) & 0xFFFF
+    u[:, 3] = _lsr(z, 48) & 0xFFFF
     u = u.reshape(-1)
     off = start - 4 * first
     return u[off: off + count]
@@ -118,6 +124,14 @@ def _units(cfg: WorkloadConfig, units: Optional[Sequence[int]]):
     return [int(u) for u in units]
 
 
+def _stack(parts, tail_shape, device, dtype=torch.float32):
+    """the parts along a new leading axis, written one by one into a tensor allocated beforehand"""
+    out = torch.empty(len(parts), *tail_shape, dtype=dtype, device=device)
+    for i, p in enumerate(parts):
+        out[i] = p
+    return out
+
+
 def _per_token(key: int, cfg: WorkloadConfig, n_tok: int, width: int, device, units, kind="normal"):
     """[S,H,n_tok,width] tensor of stream `key`, or [len(units),n_tok,width]
     for the listed flat unit ids u = s*H + h (same bits as the full tensor)."""
@@ -126,7 +140,7 @@ def _per_token(key: int, cfg: WorkloadConfig, n_tok: int, width: int, device, un
         return gen(key, (cfg.n_seq, cfg.n_head, n_tok, width), device)
     per = n_tok * width
     parts = [gen(key, (n_tok, width), device, start=u * per) for u in units]
-    return torch.stack(parts, 0) if parts else torch.empty(0, n_tok, width, device=device)
+    return _stack(parts, (n_tok, width), device)
 
 
 def _per_head(key: int, cfg: WorkloadConfig, rows: int, width: int, device, units):
@@ -185,7 +199,7 @@ def _qkv(cfg: WorkloadConfig, layer: int, scale: int, n_tok: int, device, units)
             k = student_t_tensor(kz, kc, (cfg.n_seq, cfg.n_head, n_tok, d), device)
         else:
             per = n_tok * d
-            k = torch.stack([student_t_tensor(kz, kc, (n_tok, d), device, start=u * per) for u in units], 0)
+            k = _stack([student_t_tensor(kz, kc, (n_tok, d), device, start=u * per) for u in units], (n_tok, d), device)
         q, v = gq, gv
     else:
         raise ValueError(cfg.recipe)
@@ -236,8 +250,8 @@ def make_final_scale_case(cfg: WorkloadConfig, device="cpu", units: Optional[Seq
         u = _uniform16(stream_key(s, _T_BOOST, 0, 98), 0, cfg.n_seq * cfg.n_head * hist_len, device)
         u = u.reshape(cfg.n_seq, cfg.n_head, hist_len)
     else:
-        u = torch.stack([_uniform16(stream_key(s, _T_BOOST, 0, 98), x * hist_len, hist_len, device)
-                         for x in units], 0)
+        u = _stack([_uniform16(stream_key(s, _T_BOOST, 0, 98), x * hist_len, hist_len, device) for x in units],
+                   (hist_len,), device, torch.int64)
     boosted = u < 655
     q = gq + w
     bump = w * (4.0 / float(d) ** 0.5)
@@ -269,7 +283,13 @@ def assemble_asi_case(k_history: Sequence[torch.Tensor], q_cur: torch.Tensor, k_
     n_k = q_cur.shape[-2]
     rows = asi_sample_rows(n_k, n_samp)
     q_samp = q_cur.index_select(-2, torch.tensor(rows, device=q_cur.device)).contiguous()
-    k_all = torch.cat(list(k_history) + [k_cur], dim=-2).contiguous()
+    parts = list(k_history) + [k_cur]
+    k_all = torch.empty(*k_cur.shape[:-2], sum(p.shape[-2] for p in parts), k_cur.shape[-1], dtype=k_cur.dtype,
+                        device=k_cur.device)
+    at = 0
+    for p in parts:
+        k_all[..., at: at + p.shape[-2], :] = p
+        at += p.shape[-2]
     return AsiCase(q_samp, k_all, k_all.shape[-2] - n_k, n_k, rows)
 
 
