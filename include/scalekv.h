@@ -37,8 +37,9 @@
  *   host before anything is launched, so a failing call has no side effects.
  *   scalekv_last_error() gives a message for the calling thread's last failure.
  * Limits.  head_dim must be 64 or 128; n_win <= SCALEKV_MAX_WINDOW;
- *   cache lengths and row counts are int32 and each (rows * head_dim) product
- *   must fit int32.
+ *   n_seq * n_head <= 65535 (one grid dimension counts the units; more ->
+ *   SCALEKV_ERR_UNSUPPORTED); cache lengths and row counts are int32 and each
+ *   (rows * head_dim) product must fit int32.
  */
 #ifndef SCALEKV_H
 #define SCALEKV_H

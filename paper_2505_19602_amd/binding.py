@@ -3,7 +3,10 @@
 Each function checks tensor dtype/device/contiguity (so that a pointer handed
 to C means what the header says), passes raw device pointers, sizes and the
 current HIP stream, and raises ScaleKVError on a non-OK status.  No arithmetic
-happens here.
+happens here.  Where a tensor's shape depends on how many rows a call keeps
+(idx [S,H,keep]), the binding works the number out only to check that shape
+before the call; what it returns is always the value the library wrote, and
+the two are asserted equal.
 """
 from __future__ import annotations
 
@@ -173,6 +176,7 @@ def select(shape: Shape, scores: torch.Tensor, cache_len: int, budget: int, idx:
     out = ctypes.c_int32(-1)
     _check(lib().scalekv_select(ctypes.byref(cs), _ptr(scores), int(cache_len), int(budget), _ptr(idx),
                                 ctypes.byref(out), _stream()))
+    assert out.value == keep, "the binding's shape check and the library disagree on keep"
     return int(out.value)
 
 
@@ -229,6 +233,7 @@ def step(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur: torch.Tensor
                               int(len(win_idx)), ctypes.byref(a), ctypes.byref(b), int(cache_len), int(budget),
                               ctypes.byref(c), ctypes.byref(d), ctypes.byref(new_len), _ptr(out), _ptr(idx_out),
                               wp, wb, _stream()))
+    assert new_len.value == keep + n_cur, "the binding's shape check and the library disagree on keep"
     return int(new_len.value)
 
 
@@ -298,6 +303,7 @@ class PreparedStep:
         status = self._fn(*args)
         if status != 0:
             _check(status)
+        assert self._refs[6].value == self.new_len, "the binding's shape check and the library disagree on keep"
         return self.new_len
 
 
@@ -339,6 +345,8 @@ class PreparedAppendFirst:
         status = self._fn(*args)
         if status != 0:
             _check(status)
+        assert self._refs[6].value == self.keep and bool(self._refs[7].value) == self.moved, \
+            "the binding's shape check and the library disagree on keep / moved"
         return self.keep
 
 
@@ -381,6 +389,7 @@ def select_window(shape: Shape, log_scores: torch.Tensor, cache_len: int, budget
     out = ctypes.c_int32(-1)
     _check(lib().scalekv_select_window(ctypes.byref(cs), _ptr(log_scores), int(cache_len), int(budget), f,
                                        int(len(forced)), int(pool_w), _ptr(idx), ctypes.byref(out), _stream()))
+    assert out.value == keep, "the binding's shape check and the library disagree on keep"
     return int(out.value)
 
 
@@ -409,6 +418,7 @@ def step_append_first(shape: Shape, q: torch.Tensor, k_cur: torch.Tensor, v_cur:
         ctypes.byref(a), ctypes.byref(b), int(cache_len), int(budget),
         ctypes.byref(c) if c is not None else None, ctypes.byref(d) if d is not None else None,
         ctypes.byref(keep_out), ctypes.byref(moved), _ptr(out), _ptr(idx_out), wp, wb, _stream()))
+    assert keep_out.value == keep, "the binding's shape check and the library disagree on keep"
     return int(keep_out.value), bool(moved.value)
 
 
@@ -491,4 +501,5 @@ def select_positional(shape: Shape, cache_len: int, n_sink: int, n_recent: int, 
     out = ctypes.c_int32(-1)
     _check(lib().scalekv_select_positional(ctypes.byref(cs), int(cache_len), int(n_sink), int(n_recent),
                                            _ptr(idx), ctypes.byref(out), _stream()))
+    assert out.value == keep, "the binding's shape check and the library disagree on keep"
     return int(out.value)

@@ -48,5 +48,34 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+SANITIZE_BIN = os.path.join(HERE, "sanitize_check")
+
+
+def run_sanitized() -> str:
+    """The whole library plus its driver (csrc/sanitize_main.cpp) as one executable whose HOST code
+    is built with AddressSanitizer and UndefinedBehaviorSanitizer (device code is compiled as
+    usual and never runs: the driver only exercises host-side checks and host-only routines, so
+    no GPU is needed).  Returns the driver's output, raises if anything is reported."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    cmd = [hipcc] + flags + ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                             "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer"]
+    cmd += sources() + [os.path.join(CSRC, "sanitize_main.cpp"), "-fsanitize=address", "-fsanitize=undefined",
+                        "-o", SANITIZE_BIN]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc (sanitizer build) failed:\n" + res.stderr[-4000:])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([SANITIZE_BIN], capture_output=True, text=True, env=env, timeout=600)
+    out = run.stdout + run.stderr
+    if run.returncode != 0 or "runtime error" in out or "Sanitizer" in out:
+        raise RuntimeError("the host-sanitizer build of the ABI layer reported a problem:\n" + out)
+    return out
+
+
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    import sys
+    if "--sanitize" in sys.argv:
+        print(run_sanitized().strip())
+    else:
+        print(build(force=True, verbose=True))

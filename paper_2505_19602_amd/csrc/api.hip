@@ -615,6 +615,11 @@ scalekv_status scalekv_step_append_first(const scalekv_shape* shape, const void*
         overlaps(shape, v_cache, k_next) || overlaps(shape, v_cache, v_next) ||
         overlaps(shape, k_next, v_next))
       return fail(SCALEKV_ERR_INVALID_ARG, "cache and next-cache buffers overlap");
+    // the pruning writes k_next / v_next after the attention has stored out, while q is still in use
+    for (const scalekv_kv* c : {k_next, v_next})
+      if (dense_overlaps(shape, q, n_cur, c) || dense_overlaps(shape, k_cur, n_cur, c) ||
+          dense_overlaps(shape, v_cur, n_cur, c) || dense_overlaps(shape, out, n_cur, c))
+        return fail(SCALEKV_ERR_INVALID_ARG, "q, k_cur, v_cur or out overlaps a next-cache buffer that is written");
   }
 
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -127,11 +127,6 @@ __global__ __launch_bounds__(256) void attend_simple_kernel(
 // matching V^T operand is one contiguous 16-byte LDS read.
 // =====================================================================
 constexpr int BN = 64;
-constexpr float kRescaleThreshold = 8.f;  // log2 units a row max may grow before O is rescaled
-
-__device__ __forceinline__ int pi32(int i) {  // swap bits 2 and 3
-  return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
-}
 
 template <int D>
 struct AttendLds {

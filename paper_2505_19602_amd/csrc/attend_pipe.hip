@@ -84,13 +84,8 @@ constexpr int kRowBytes = D * 2;     // 256
 constexpr int kTileBytes = TN * kRowBytes;  // 16 KB
 constexpr int kStages = 2;
 constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // K stages then V stages: 64 KB
-constexpr float kRescaleThreshold = 8.f;
 constexpr float kBlockSumLimit = 1099511627776.f;  // 2^40: largest row-sum share a block may add unchecked
 constexpr int kXcds = 8;
-
-__device__ __forceinline__ int pi32(int i) {  // swap bits 2 and 3
-  return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
-}
 
 // Three-input max as one instruction and without the NaN-quieting pre-pass the
 // compiler puts in front of fmaxf on values it has not produced itself.

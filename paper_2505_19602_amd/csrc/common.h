@@ -123,6 +123,13 @@ hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, Kv
 inline bool attend_uses_pipe(int dtype, int d, int n_q) { return dtype == 1 && d == 128 && n_q > 128; }
 
 // ---- device helpers ----
+// Shared by the two MFMA attention kernels: the key row fed to MFMA row i of the first product
+// is row pi32(i) of the 32-key block (bits 2 and 3 swapped), which makes the registers of an
+// S^T block the B operand of the second product; and the number of log2 units a row maximum may
+// grow before the running offset is moved and the accumulators are rescaled.
+__device__ __forceinline__ int pi32(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
+constexpr float kRescaleThreshold = 8.f;
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
   return __uint_as_float(bits16 << 16);
 }

@@ -273,3 +273,24 @@ def test_step_and_compact_reject_inputs_that_overlap_the_destination(L):
     assert L.scalekv_compact(ctypes.byref(s), ctypes.byref(src_k), ctypes.byref(src_v), 20, None, 5, p(0x300000), p(0x700000),
                              8, ctypes.byref(dst_k), ctypes.byref(dst_v), None) == 1
     assert "overlap a destination" in _err(L)
+
+
+def test_step_append_first_rejects_inputs_that_overlap_the_next_cache(L):
+    # the final pruning writes k_next / v_next after the attention has stored `out`
+    s = _shape()
+    p = ctypes.c_void_p
+    big = ctypes.c_size_t(1 << 30)
+    k_cache, v_cache = _kv(0x100000), _kv(0x200000)
+    k_next, v_next = _kv(0x300000), _kv(0x400000)
+    win = (ctypes.c_int32 * 1)(0)
+    keep, moved = ctypes.c_int32(-1), ctypes.c_int32(-1)
+
+    def step(q, kc, vc, out, budget=5):
+        return L.scalekv_step_append_first(ctypes.byref(s), p(q), p(kc), p(vc), 8, win, 1, 1, ctypes.byref(k_cache),
+                                           ctypes.byref(v_cache), 20, budget, ctypes.byref(k_next),
+                                           ctypes.byref(v_next), ctypes.byref(keep), ctypes.byref(moved), p(out), None,
+                                           p(0x800000), big, None)
+    assert step(0x500000, 0x600000, 0x700000, 0x300000 + 1024) == 1 and "next-cache" in _err(L)     # out in k_next
+    assert step(0x400000 + 512, 0x600000, 0x700000, 0x900000) == 1                                    # q in v_next
+    assert step(0x500000, 0x600000, 0x300000, 0x900000) == 1                                          # v_cur in k_next
+
