@@ -248,6 +248,40 @@ def run_cases(args, torch, skv) -> int:
     return 0
 
 
+def attend_alone(args, torch, skv) -> int:
+    """--attend-alone N_Q,KV_LEN: the pipelined attention kernel by itself (scalekv_attend, one key
+    segment, nothing else to carry) on 16 x 16 units of seeded normal data, or of zeros with
+    --zero-keys (the same instruction stream switching fewer bits).  With --library it runs one of
+    the measurement-only builds of `python -m paper_2505_19602_amd.build --variant ...`, whose
+    results are wrong on purpose: timing only.  One JSON line."""
+    import workloads as W
+    dev, dt = "cuda", torch.bfloat16
+    S, H, d = args.case_seqs, args.case_heads, 128
+    n_q, kv = (int(x) for x in args.attend_alone.split(","))
+    shape = skv.Shape(S, H, d, dt)
+    mk = lambda key, rows: W.normal_tensor(W.stream_key(4242, key), (S, H, rows, d), dev).to(dt)
+    q, k, v = mk(1, n_q), mk(2, kv), mk(3, kv)
+    if args.zero_keys:
+        k.zero_()
+    out = torch.empty_like(q)
+    for _ in range(3):
+        skv.attend(shape, q, k, v, kv, out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(args.reps):
+        skv.attend(shape, q, k, v, kv, out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.reps
+    flops = 4.0 * n_q * kv * d * S * H
+    print(json.dumps({"mode": "attend-alone", "library": os.path.basename(skv.lib_path()), "zero_keys": bool(args.zero_keys),
+                      "units": S * H, "n_q": n_q, "kv_len": kv, "reps": args.reps, "ms": ms,
+                      "tflops": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}),
+          flush=True)
+    return 0
+
+
 def parity_replay(torch, skv, W, cfg, shape, inputs, prefix, bufs, table, lens_before_last, windows, ws,
                   n_units: int = 2, n_rows: int = 48):
     """After the timed region: the last scale's call of one drafter layer and one refiner layer is
@@ -328,7 +362,11 @@ def main() -> int:
                     help="skip the replay of sampled last-scale units through the CPU oracle after the timed region")
     ap.add_argument("--cases", default=None,
                     help="cache_len,budget,n_cur[;...]: only run these step shapes on random inputs (for rocprofv3)")
-    ap.add_argument("--reps", type=int, default=3, help="calls per shape of --cases")
+    ap.add_argument("--reps", type=int, default=3, help="calls per shape of --cases / timed calls of --attend-alone")
+    ap.add_argument("--attend-alone", default=None, help="N_Q,KV_LEN: time the pipelined attention kernel by itself")
+    ap.add_argument("--zero-keys", action="store_true", help="--attend-alone with all keys zero")
+    ap.add_argument("--library", default=None,
+                    help="path of a measurement-only build of the library to load instead of the in-tree one")
     ap.add_argument("--case-seqs", type=int, default=16)
     ap.add_argument("--case-heads", type=int, default=16)
     args = ap.parse_args()
@@ -336,6 +374,11 @@ def main() -> int:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 
+    if args.library:
+        if not (args.attend_alone or args.cases):
+            print("--library is for --attend-alone / --cases runs only: those builds give wrong results", file=sys.stderr)
+            return 2
+        os.environ["SCALEKV_LIBRARY"] = os.path.abspath(args.library)
     import torch
     import paper_2505_19602_amd as skv
     import workloads as W
@@ -344,6 +387,8 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
     dev = "cuda"
+    if args.attend_alone:
+        return attend_alone(args, torch, skv)
     if args.cases:
         return run_cases(args, torch, skv)
     cfg = W.get_config(args.config)

@@ -74,7 +74,9 @@ _lib: Optional[ctypes.CDLL] = None
 
 
 def lib_path() -> str:
-    return os.path.join(HERE, "libscalekv.so")
+    """The library built in-tree.  SCALEKV_LIBRARY (a path) overrides it: a measurement aid for
+    the ablation builds of `build.py --variant`, whose results are wrong on purpose."""
+    return os.environ.get("SCALEKV_LIBRARY") or os.path.join(HERE, "libscalekv.so")
 
 
 def lib() -> ctypes.CDLL:

@@ -48,6 +48,29 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+# Measurement-only builds of the whole library with one ingredient of the pipelined attention
+# kernel taken out (see attend_pipe.hip); written beside the real library under another name and
+# only ever loaded when SCALEKV_LIBRARY names them (bench.py --attend-alone does that on request).
+VARIANTS = {
+    "no_softmax": ["-DSCALEKV_ABLATE_SOFTMAX"],
+    "no_transfer": ["-DSCALEKV_ABLATE_TRANSFER"],
+    "one_wg_per_cu": ["-DSCALEKV_ONE_WG_PER_CU"],
+}
+
+
+def variant_path(name: str) -> str:
+    return os.path.join(HERE, f"libscalekv_{name}.so")
+
+
+def build_variant(name: str) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + VARIANTS[name] + sources() + ["-o", variant_path(name)]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
+    return variant_path(name)
+
+
 SANITIZE_BIN = os.path.join(HERE, "sanitize_check")
 
 
@@ -77,5 +100,8 @@ if __name__ == "__main__":
     import sys
     if "--sanitize" in sys.argv:
         print(run_sanitized().strip())
+    elif "--variant" in sys.argv:
+        for name in sys.argv[sys.argv.index("--variant") + 1:]:
+            print(build_variant(name))
     else:
         print(build(force=True, verbose=True))
