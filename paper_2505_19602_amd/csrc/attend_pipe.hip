@@ -453,24 +453,38 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- normalise and write: lane owns query column j, channels 32db + 8(r/4) + 4h + r%4
+  // ---- normalise and write.  A lane owns query column j, channels 32db + 8(r/4) + 4h + r%4:
+  // sixteen 8-byte pieces of its output row.  Stored from there, every instruction of the wave
+  // would touch 32 rows with 16 bytes each; instead the wave turns its 32 x 128 block round in
+  // LDS (the tile stages are free: every wave has left its last tile; each wave uses a region of
+  // its own, rows padded to 272 bytes against bank conflicts) and writes whole 256-byte rows,
+  // 16 bytes per lane.
   {
-    const int row = q_base + j;
+    constexpr int kOutRowStride = kRowBytes + 16;
+    unsigned char* const ostage = smem + wave * (32 * kOutRowStride);
     const float l_tot = both_halves_sum(l_run);
-    if (row < n_q) {
-      const float inv = 1.f / l_tot;
-      uint16_t* orow = out + ((long long)unit * n_q + row) * D;
+    const float inv = 1.f / l_tot;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const bf16x2 lo = {(__bf16)(o[db][4 * g] * inv), (__bf16)(o[db][4 * g + 1] * inv)};
-          const bf16x2 hi = {(__bf16)(o[db][4 * g + 2] * inv), (__bf16)(o[db][4 * g + 3] * inv)};
-          uint2 pk;
-          pk.x = __builtin_bit_cast(uint32_t, lo);
-          pk.y = __builtin_bit_cast(uint32_t, hi);
-          *(uint2*)(orow + 32 * db + 8 * g + 4 * h) = pk;
-        }
+      for (int g = 0; g < 4; ++g) {
+        const bf16x2 lo = {(__bf16)(o[db][4 * g] * inv), (__bf16)(o[db][4 * g + 1] * inv)};
+        const bf16x2 hi = {(__bf16)(o[db][4 * g + 2] * inv), (__bf16)(o[db][4 * g + 3] * inv)};
+        uint2 pk;
+        pk.x = __builtin_bit_cast(uint32_t, lo);
+        pk.y = __builtin_bit_cast(uint32_t, hi);
+        *(uint2*)(ostage + j * kOutRowStride + 64 * db + 16 * g + 8 * h) = pk;
+      }
+    // the wave's own LDS writes have landed before it reads them back (same wave: no barrier)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    unsigned char* const obase = (unsigned char*)(out + ((long long)unit * n_q + q_base) * D);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const int r = 4 * p + (lane >> 4);
+      const u32x4 val = *(const u32x4*)(ostage + r * kOutRowStride + 16 * (lane & 15));
+      if (q_base + r < n_q) *(u32x4*)(obase + (long long)r * kRowBytes + 16 * (lane & 15)) = val;
     }
   }
   __builtin_amdgcn_sched_barrier(0);
