@@ -254,17 +254,35 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
       v_ofs[db] = (8 * h + g) * kRowBytes + 64 * (db ^ g) + 32 * (j >> 4) + 8 * (i & 3);
   }
 
-  // ---- Q fragments: B operand of the first product, resident for the whole kernel
+  // ---- Q fragments: B operand of the first product, resident for the whole kernel.  A lane's
+  // fragments are eight 16-byte pieces of its query row, 32 bytes apart: fetched as such, every
+  // instruction of the wave would touch 32 rows with 32 bytes each.  Instead the wave's 32 rows
+  // go, whole and 16 bytes per lane, straight into LDS and are read from there once the first
+  // tile has arrived.  They wait in the second stage, which is not in use before the first
+  // barrier, each wave's rows exactly where the same wave will later put its share of the second
+  // tile (16 K rows and 16 V rows, 4 KB each): nobody else writes there, so no barrier is needed
+  // before that tile is requested, only the wave's own reads must have returned.  Chunk c of row
+  // r sits in slot c ^ (r & 15), so that the fragment reads are free of bank conflicts.  Rows
+  // past the end of the map repeat its last row; nothing is stored for them.
   bf16x8 qf[8];
+  unsigned char* const q_stage_k = k_lds + kTileBytes + (16 * wave) * kRowBytes;  // query rows 0-15 of the wave
+  unsigned char* const q_stage_v = v_lds + kTileBytes + (16 * wave) * kRowBytes;  // query rows 16-31
   {
-    const int row = q_base + j;
+    const unsigned qk = __builtin_amdgcn_readfirstlane(lds_addr(q_stage_k));
+    const unsigned qv = __builtin_amdgcn_readfirstlane(lds_addr(q_stage_v));
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      uint4 raw = make_uint4(0, 0, 0, 0);
-      if (row < n_q) raw = *(const uint4*)(qu + (long long)row * D + 16 * s + 8 * h);
-      qf[s] = __builtin_bit_cast(bf16x8, raw);
+    for (int p = 0; p < 8; ++p) {
+      const int r = 4 * p + (lane >> 4);
+      const unsigned row = (unsigned)min(q_base + r, n_q - 1);
+      dma16<0>((const unsigned char*)qu, row * kRowBytes + 16 * ((lane & 15) ^ (r & 15)),
+               (p < 4 ? qk : qv) + 4 * (p & 3) * kRowBytes);
     }
   }
+  auto read_q = [&]() __attribute__((always_inline)) {
+    const unsigned char* row = (j < 16 ? q_stage_k : q_stage_v) + (j & 15) * kRowBytes;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8*)(row + 16 * ((2 * s + h) ^ (j & 15)));
+  };
 
   f32x16 o[4];
   float m_run;  // exponent offset
@@ -406,7 +424,9 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   };
   // One pass over all tiles.  The first tile always follows its maxima: that is where
   // m_run comes from.
-  auto pass = [&](auto tracked) __attribute__((always_inline)) {
+  // `first` (a std::bool_constant): the query rows are waiting in LDS and are taken into registers
+  // before the second tile may overwrite them.
+  auto pass = [&](auto tracked, auto first) __attribute__((always_inline)) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -416,6 +436,10 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     issue_tile(0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    if constexpr (decltype(first)::value) {
+      read_q();
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragments are in registers, their space may be refilled
+    }
     if (n_tile > 1) issue_tile(1);
     fetch_k(kf, 0);
     tile(std::true_type{}, 0, 0, kTileBytes);
@@ -426,9 +450,9 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     }
     if (t < n_tile) tile(tracked, t, kTileBytes, 0);
   };
-  pass(std::false_type{});
+  pass(std::false_type{}, std::true_type{});
   // every wave has left its last tile when the votes are in, so the stages may be refilled
-  if (__syncthreads_or(overflowed != 0)) pass(std::true_type{});
+  if (__syncthreads_or(overflowed != 0)) pass(std::true_type{}, std::false_type{});
 
   // ---- append, first half: this workgroup's share of the second segment goes behind the first,
   // as 16-byte vectors.  The vectors of the first round (the whole share when it is at most 128
