@@ -302,8 +302,13 @@ def test_step_chain_2b_1024_full_size_sampled_units():
 
 
 def test_step_long_cache_and_other_shapes():
-    """cache longer than the fused select holds in LDS; head_dim 64 in bf16; fp32 with head_dim 128"""
-    for dtype, d, L, n_cur, budget in ((torch.bfloat16, 128, 13000, 40, 700), (torch.bfloat16, 64, 900, 150, 333),
+    """The routes of the ranking besides the one-launch kernel: a cache longer than the select holds in
+    LDS (logits, finalise, select from global, compact); a cache of a length the one-launch kernel
+    leaves to the logits + fused-select pair when there are few units (and the same with many
+    queries, so that the pipelined attention follows the separate compaction); head_dim 64 in bf16;
+    fp32 with head_dim 128."""
+    for dtype, d, L, n_cur, budget in ((torch.bfloat16, 128, 13000, 40, 700), (torch.bfloat16, 128, 5000, 40, 500),
+                                       (torch.bfloat16, 128, 4500, 200, 1000), (torch.bfloat16, 64, 900, 150, 333),
                                        (torch.float32, 128, 300, 50, 64)):
         _note(f"step dtype={dtype} d={d} L={L} n_cur={n_cur} budget={budget}")
         S, H = 1, 2
