@@ -275,11 +275,48 @@ def attend_alone(args, torch, skv) -> int:
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.reps
     flops = 4.0 * n_q * kv * d * S * H
-    print(json.dumps({"mode": "attend-alone", "library": os.path.basename(skv.lib_path()), "zero_keys": bool(args.zero_keys),
-                      "units": S * H, "n_q": n_q, "kv_len": kv, "reps": args.reps, "ms": ms,
-                      "tflops": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}),
-          flush=True)
+    line = {"mode": "attend-alone", "library": os.path.basename(skv.lib_path()), "zero_keys": bool(args.zero_keys),
+            "units": S * H, "n_q": n_q, "kv_len": kv, "reps": args.reps, "ms": ms,
+            "tflops": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    if args.timeline:
+        line["timeline"] = timeline_summary(skv, (n_q + 127) // 128 * S * H)
+    print(json.dumps(line), flush=True)
     return 0
+
+
+def timeline_summary(skv, n_wg: int) -> dict:
+    """Per-workgroup records of the last attention launch, from a library built with
+    `--variant timeline` (four readings of the 100 MHz counter and the hardware id register per
+    workgroup), summed up per XCD: hardware hands workgroup i to XCD i mod 8."""
+    import ctypes
+
+    import numpy as np
+    L = skv.lib()
+    if not hasattr(L, "scalekv_timeline_read"):
+        raise SystemExit("--timeline needs --library <a build made with --variant timeline>")
+    rec = np.zeros((n_wg, 5), dtype=np.uint64)
+    rc = L.scalekv_timeline_read(rec.ctypes.data_as(ctypes.c_void_p), ctypes.c_int(n_wg))
+    if rc != 0:
+        raise SystemExit(f"scalekv_timeline_read returned {rc}")
+    t = (rec[:, :4].astype(np.int64) - int(rec[:, 0].min())) * 0.01  # us since the first workgroup started
+    hw = rec[:, 4].astype(np.int64)
+    xcd = np.arange(n_wg) % 8
+    cu = (((hw >> 13) & 7) * 2 + ((hw >> 12) & 1)) * 16 + ((hw >> 8) & 15)  # within the XCD
+    span = float(t[:, 3].max())
+    dur = t[:, 3] - t[:, 0]
+    n_cu = sum(len(np.unique(cu[xcd == x])) for x in range(8))
+    per_xcd = [{"xcd": x, "workgroups": int((xcd == x).sum()), "mean_wg_us": round(float(dur[xcd == x].mean()), 1),
+                "last_end_us": round(float(t[xcd == x, 3].max()), 1)} for x in range(8) if (xcd == x).any()]
+    ends = [p["last_end_us"] for p in per_xcd]
+    return {"workgroups": n_wg, "compute_units": n_cu, "span_us": round(span, 1),
+            "wg_us": {"mean": round(float(dur.mean()), 1), "min": round(float(dur.min()), 1), "max": round(float(dur.max()), 1)},
+            "start_to_first_tile_us": round(float((t[:, 1] - t[:, 0]).mean()), 2),
+            "tile_loop_us": round(float((t[:, 2] - t[:, 1]).mean()), 1),
+            "loop_end_to_end_us": round(float((t[:, 3] - t[:, 2]).mean()), 2),
+            "slot_occupancy": round(float(dur.sum() / (2 * n_cu * span)), 3),
+            "tile_loop_share_of_slot_time": round(float((t[:, 2] - t[:, 1]).sum() / (2 * n_cu * span)), 3),
+            "per_xcd": per_xcd,
+            "idle_at_the_end": round(float(1.0 - np.mean(ends) / span), 4)}
 
 
 def parity_replay(torch, skv, W, cfg, shape, inputs, prefix, bufs, table, lens_before_last, windows, ws,
@@ -365,6 +402,8 @@ def main() -> int:
     ap.add_argument("--reps", type=int, default=3, help="calls per shape of --cases / timed calls of --attend-alone")
     ap.add_argument("--attend-alone", default=None, help="N_Q,KV_LEN: time the pipelined attention kernel by itself")
     ap.add_argument("--zero-keys", action="store_true", help="--attend-alone with all keys zero")
+    ap.add_argument("--timeline", action="store_true",
+                    help="--attend-alone with a --variant timeline build: per-XCD summary of the workgroups' start and end times")
     ap.add_argument("--library", default=None,
                     help="path of a measurement-only build of the library to load instead of the in-tree one")
     ap.add_argument("--case-seqs", type=int, default=16)

@@ -55,6 +55,7 @@ VARIANTS = {
     "no_softmax": ["-DSCALEKV_ABLATE_SOFTMAX"],
     "no_transfer": ["-DSCALEKV_ABLATE_TRANSFER"],
     "one_wg_per_cu": ["-DSCALEKV_ONE_WG_PER_CU"],
+    "timeline": ["-DSCALEKV_TIMELINE"],
 }
 
 

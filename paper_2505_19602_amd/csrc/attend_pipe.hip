@@ -91,10 +91,21 @@ constexpr int kStages = 2;
 //   SCALEKV_ABLATE_TRANSFER   only the first two key tiles are fetched; later tiles re-use them
 //   SCALEKV_ONE_WG_PER_CU     the workgroup claims more than half of the LDS, so that one
 //                             workgroup runs per compute unit (results stay correct)
+//   SCALEKV_TIMELINE          every workgroup records when it started, when its first tile had
+//                             arrived, when it left the tile loop and when it ended (results stay
+//                             correct); scalekv_timeline_read() hands the records to the host
 #if defined(SCALEKV_ONE_WG_PER_CU)
 constexpr int kLdsBytes = 96 * 1024;
 #else
 constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // K stages then V stages: 64 KB
+#endif
+#if defined(SCALEKV_TIMELINE)
+constexpr int kTimelineMaxWg = 8192;
+constexpr int kTimelineWords = 5;  // four readings of the 100 MHz counter, then the hardware id register
+__device__ unsigned long long g_timeline[kTimelineMaxWg * kTimelineWords];
+#define SCALEKV_STAMP(name) const unsigned long long name = __builtin_amdgcn_s_memrealtime()
+#else
+#define SCALEKV_STAMP(name)
 #endif
 constexpr float kBlockSumLimit = 1099511627776.f;  // 2^40: largest row-sum share a block may add unchecked
 constexpr int kXcds = 8;
@@ -165,6 +176,10 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
                         long long v_head_stride, int len1, const uint16_t* __restrict__ k2,
                         const uint16_t* __restrict__ v2, int len2, int append, int n_head,
                         int n_qtile, int n_wg, float scale_log2e, uint16_t* __restrict__ out) {
+  SCALEKV_STAMP(t_start);
+#if defined(SCALEKV_TIMELINE)
+  unsigned long long t_first_tile = 0;
+#endif
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* const k_lds = smem;
   unsigned char* const v_lds = smem + kStages * kTileBytes;
@@ -437,6 +452,9 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if constexpr (decltype(first)::value) {
+#if defined(SCALEKV_TIMELINE)
+      t_first_tile = __builtin_amdgcn_s_memrealtime();
+#endif
       read_q();
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the fragments are in registers, their space may be refilled
     }
@@ -453,6 +471,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   pass(std::false_type{}, std::true_type{});
   // every wave has left its last tile when the votes are in, so the stages may be refilled
   if (__syncthreads_or(overflowed != 0)) pass(std::true_type{}, std::false_type{});
+  SCALEKV_STAMP(t_loop_end);
 
   // ---- append, first half: this workgroup's share of the second segment goes behind the first,
   // as 16-byte vectors.  The vectors of the first round (the whole share when it is at most 128
@@ -542,6 +561,17 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
       }
     }
   }
+#if defined(SCALEKV_TIMELINE)
+  __builtin_amdgcn_s_waitcnt(0);  // the workgroup's stores have been issued and acknowledged
+  if (tid == 0 && blockIdx.x < kTimelineMaxWg) {
+    unsigned long long* rec = g_timeline + (long long)blockIdx.x * kTimelineWords;
+    rec[0] = t_start;
+    rec[1] = t_first_tile;
+    rec[2] = t_loop_end;
+    rec[3] = __builtin_amdgcn_s_memrealtime();
+    rec[4] = __builtin_amdgcn_s_getreg((31 << 11) | 4);  // HW_ID: compute unit, shader array, shader engine
+  }
+#endif
 }
 
 }  // namespace
@@ -572,3 +602,14 @@ hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, Kv
 }
 
 }  // namespace scalekv
+
+#if defined(SCALEKV_TIMELINE)
+// Measurement-only builds: copies the records of workgroups 0 .. n_wg-1 of the most recent
+// attend_pipe_kernel launch (kTimelineWords words each) to host memory.  Synchronises the device.
+extern "C" int scalekv_timeline_read(unsigned long long* dst, int n_wg) {
+  if (!dst || n_wg < 0 || n_wg > scalekv::kTimelineMaxWg) return -1;
+  if (hipDeviceSynchronize() != hipSuccess) return -2;
+  return hipMemcpyFromSymbol(dst, HIP_SYMBOL(scalekv::g_timeline),
+                             sizeof(unsigned long long) * scalekv::kTimelineWords * n_wg) == hipSuccess ? 0 : -2;
+}
+#endif
