@@ -56,6 +56,7 @@ VARIANTS = {
     "no_transfer": ["-DSCALEKV_ABLATE_TRANSFER"],
     "one_wg_per_cu": ["-DSCALEKV_ONE_WG_PER_CU"],
     "timeline": ["-DSCALEKV_TIMELINE"],
+    "timeline_no_transfer": ["-DSCALEKV_TIMELINE", "-DSCALEKV_ABLATE_TRANSFER"],
 }
 
 
