@@ -56,6 +56,8 @@ VARIANTS = {
     "no_transfer": ["-DSCALEKV_ABLATE_TRANSFER"],
     "one_wg_per_cu": ["-DSCALEKV_ONE_WG_PER_CU"],
     "timeline": ["-DSCALEKV_TIMELINE"],
+    # every grid walked backwards; results must be bit-identical (tests/test_gpu_wg_order.py)
+    "reversed_order": ["-DSCALEKV_REVERSE_WG"],
     "timeline_no_transfer": ["-DSCALEKV_TIMELINE", "-DSCALEKV_ABLATE_TRANSFER"],
 }
 

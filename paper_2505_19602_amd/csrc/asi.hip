@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void asi_terms_kernel(ScoreWorkspace ws, 
   __shared__ float red[kWaves];
   __shared__ float shift_s;
 
-  const int row = blockIdx.x, unit = blockIdx.y;
+  const int row = SCALEKV_WG_X, unit = SCALEKV_WG_Y;
   const int tid = threadIdx.x;
   const float* lg = ws.logits + (long long)unit * ws.len_pad * kMaxWindow + row;
   auto logit = [&](int i) -> float { return lg[(long long)i * kMaxWindow]; };

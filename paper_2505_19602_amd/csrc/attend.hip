@@ -32,10 +32,10 @@ __global__ __launch_bounds__(256) void attend_simple_kernel(
   __shared__ float vs[BK][D];
   __shared__ float ps[BQ][BK + 1];
 
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int seq = unit / n_head, head = unit - seq * n_head;
   const int tid = threadIdx.x, r = tid / G, g = tid % G;
-  const int q0 = blockIdx.x * BQ;
+  const int q0 = SCALEKV_WG_X * BQ;
   const T* qu = q + (long long)unit * n_q * D;
   const T* ku = k + seq * k_seq_stride + head * k_head_stride;
   const T* vu = v + seq * v_seq_stride + head * v_head_stride;
@@ -152,11 +152,11 @@ __global__ __launch_bounds__(256) void attend_mfma_kernel(
   uint16_t* const k_lds0 = smem;
   uint16_t* const vt_lds0 = smem + 2 * L::kTileK;
 
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int seq = unit / n_head, head = unit - seq * n_head;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
-  const int q_base = blockIdx.x * (128 * QB) + wave * (32 * QB);
+  const int q_base = SCALEKV_WG_X * (128 * QB) + wave * (32 * QB);
   const uint16_t* qu = q + (long long)unit * n_q * D;
   const uint16_t* ku = k + seq * k_seq_stride + head * k_head_stride;
   const uint16_t* vu = v + seq * v_seq_stride + head * v_head_stride;

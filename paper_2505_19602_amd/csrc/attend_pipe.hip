@@ -186,7 +186,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
 
   // Consecutive workgroup ids go round-robin over the XCDs.  Renumber so that the ids an
   // XCD receives are consecutive: all query tiles of a unit then share one L2.
-  int wg = blockIdx.x;
+  int wg = SCALEKV_WG_X;
   {
     const int per = n_wg / kXcds, full = per * kXcds;  // the tail (< 8 groups) keeps its ids
     if (wg < full) wg = (wg % kXcds) * per + wg / kXcds;

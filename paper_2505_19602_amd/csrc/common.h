@@ -123,6 +123,19 @@ hipError_t launch_attend_pipe(int n_unit, int n_head, const void* q, int n_q, Kv
 inline bool attend_uses_pipe(int dtype, int d, int n_q) { return dtype == 1 && d == 128 && n_q > 128; }
 
 // ---- device helpers ----
+// Workgroup coordinates as the kernels read them.  A build with SCALEKV_REVERSE_WG
+// (python -m paper_2505_19602_amd.build --variant reversed_order) walks every grid backwards:
+// workgroup i does the work that workgroup n-1-i does in the plain build.  No result may depend
+// on which workgroup runs first; a test compares the two builds bit for bit.
+#if defined(SCALEKV_REVERSE_WG)
+#define SCALEKV_WG_X ((int)(gridDim.x - 1 - blockIdx.x))
+#define SCALEKV_WG_Y ((int)(gridDim.y - 1 - blockIdx.y))
+#define SCALEKV_WG_Z ((int)(gridDim.z - 1 - blockIdx.z))
+#else
+#define SCALEKV_WG_X ((int)blockIdx.x)
+#define SCALEKV_WG_Y ((int)blockIdx.y)
+#define SCALEKV_WG_Z ((int)blockIdx.z)
+#endif
 // Shared by the two MFMA attention kernels: the key row fed to MFMA row i of the first product
 // is row pi32(i) of the 32-key block (bits 2 and 3 swapped), which makes the registers of an
 // S^T block the B operand of the second product; and the number of log2 units a row maximum may

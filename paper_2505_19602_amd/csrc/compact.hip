@@ -30,9 +30,9 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(Side k_side, Side v_s
                                                            const int32_t* __restrict__ idx,
                                                            int keep, int n_cur, int n_head,
                                                            int vec_per_row_log2) {
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int seq = unit / n_head, head = unit - seq * n_head;
-  const Side side = blockIdx.z != 0 ? v_side : k_side;
+  const Side side = SCALEKV_WG_Z != 0 ? v_side : k_side;
   const vec4* __restrict__ src = side.src + seq * side.src_seq_stride + head * side.src_head_stride;
   const vec4* __restrict__ cur = side.cur;
   vec4* __restrict__ dst = side.dst + seq * side.dst_seq_stride + head * side.dst_head_stride;
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(Side k_side, Side v_s
   const int32_t* uidx = idx ? idx + (long long)unit * keep : nullptr;
   const int total = (keep + n_cur) << vec_per_row_log2;
 
-  int f0 = (blockIdx.x * kThreads * kUnroll) + threadIdx.x;
+  int f0 = (SCALEKV_WG_X * kThreads * kUnroll) + threadIdx.x;
   vec4 val[kUnroll];
   bool ok[kUnroll];
 #pragma unroll

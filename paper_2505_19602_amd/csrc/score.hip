@@ -29,7 +29,7 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
   __shared__ float red_max[kThreads / 64][kMaxWindow];
   __shared__ float red_sum[kThreads / 64][kMaxWindow];
 
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int seq = unit / n_head, head = unit - seq * n_head;
   const int tid = threadIdx.x;
   const T* qu = q + unit * q_unit_stride;
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
   }
   __syncthreads();
 
-  const int key = blockIdx.x * kThreads + tid;
+  const int key = SCALEKV_WG_X * kThreads + tid;
   const bool valid = key < cache_len;
   const int krow = valid ? key : cache_len - 1;  // clamp: load something legal, ignore it later
   const uint4* kv = (const uint4*)(k + seq * k_seq_stride + head * k_head_stride +
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void score_logits_kernel(
     float ssum = 0.f;
     for (int w = 0; w < kThreads / 64; ++w)
       if (red_max[w][tid] > -INFINITY) ssum += red_sum[w][tid] * expf(red_max[w][tid] - m);
-    float* part = ws.partial + ((long long)unit * ws.n_chunk + blockIdx.x) * 2 * kMaxWindow;
+    float* part = ws.partial + ((long long)unit * ws.n_chunk + SCALEKV_WG_X) * 2 * kMaxWindow;
     part[tid] = m;
     part[kMaxWindow + tid] = ssum;
   }
@@ -106,14 +106,14 @@ __global__ __launch_bounds__(kThreads) void score_logits_mfma_kernel(
   constexpr int NT = 4;  // 16-key tiles per wave
   __shared__ float red_max[kThreads / 64][kMaxWindow];
   __shared__ float red_sum[kThreads / 64][kMaxWindow];
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int seq = unit / n_head, head = unit - seq * n_head;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint16_t* ku = k + seq * k_seq_stride + head * k_head_stride;
   score_bf16x8 qf[D / 32];
   score_load_window<D>(q + unit * q_unit_stride, rows, n_win, qf);
   float m, e;
-  score_wave_logits<D, NT>(ku, qf, blockIdx.x * kScoreChunk + wave * (16 * NT), cache_len, sm_scale,
+  score_wave_logits<D, NT>(ku, qf, SCALEKV_WG_X * kScoreChunk + wave * (16 * NT), cache_len, sm_scale,
                            ws.logits + (long long)unit * ws.len_pad * kMaxWindow, m, e);
   if (lane < kMaxWindow) { red_max[wave][lane] = m; red_sum[wave][lane] = e; }
   __syncthreads();
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void score_logits_mfma_kernel(
     float ssum = 0.f;
     for (int w = 0; w < kThreads / 64; ++w)
       if (red_max[w][tid] > -INFINITY) ssum += red_sum[w][tid] * expf(red_max[w][tid] - mm);
-    float* part = ws.partial + ((long long)unit * ws.n_chunk + blockIdx.x) * 2 * kMaxWindow;
+    float* part = ws.partial + ((long long)unit * ws.n_chunk + SCALEKV_WG_X) * 2 * kMaxWindow;
     part[tid] = mm;
     part[kMaxWindow + tid] = ssum;
   }
@@ -135,11 +135,11 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(int n_win, int cach
                                                              float* __restrict__ log_scores,
                                                              long long score_unit_stride) {
   __shared__ float row_shift[kMaxWindow];  // max_j + log Z_j
-  const int unit = blockIdx.y;
+  const int unit = SCALEKV_WG_Y;
   const int tid = threadIdx.x;
   if (tid < kMaxWindow) row_shift[tid] = tid < n_win ? score_row_shift(ws, unit, tid) : 0.f;
   __syncthreads();
-  const int key = blockIdx.x * 256 + tid;
+  const int key = SCALEKV_WG_X * 256 + tid;
   if (key >= cache_len) return;
   log_scores[unit * score_unit_stride + key] = score_log_sum(ws, unit, key, n_win, row_shift);
 }

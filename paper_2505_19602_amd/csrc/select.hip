@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
   __shared__ uint32_t wave_gt[kWaves], wave_eq[kWaves];
   __shared__ float red_max[SCORE_D ? kWaves : 1][kMaxWindow], red_sum[SCORE_D ? kWaves : 1][kMaxWindow];
 
-  const int unit = blockIdx.x;
+  const int unit = SCALEKV_WG_X;
   const int tid = threadIdx.x;
   const float* s = scores + unit * score_unit_stride;
   const int pool_r = (ex.pool_w - 1) / 2;
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(const float* __restric
 }
 
 __global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total) {
-  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long e = (long long)SCALEKV_WG_X * blockDim.x + threadIdx.x;
   if (e < total) idx[e] = (int32_t)(e % keep);
 }
 
@@ -244,7 +244,7 @@ __global__ void iota_kernel(int32_t* __restrict__ idx, int keep, long long total
 // keep - n_sink positions of its cache_len rows.
 __global__ void positional_kernel(int32_t* __restrict__ idx, int keep, int n_sink, int cache_len,
                                   long long total) {
-  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long e = (long long)SCALEKV_WG_X * blockDim.x + threadIdx.x;
   if (e >= total) return;
   const int t = (int)(e % keep);
   idx[e] = t < n_sink ? t : cache_len - keep + t;
