@@ -51,3 +51,40 @@ def test_stage_lists_match_the_event_slots_of_the_library_hook():
         stages = bench.STAGES[variant]
         assert "attend" in stages
         assert len(stages) + 1 <= 5       # the step hook marks at most five boundaries
+
+
+def test_timeline_summary_reads_per_xcd_times_from_the_records():
+    """Synthetic records of a 2-round launch on 8 XCDs x 2 compute units x 2 slots: XCD x's
+    workgroups last 100 + 10 x us, so the launch ends with XCD 7 and the others idle before that."""
+    import ctypes
+
+    import numpy as np
+    bench = _bench_module()
+    n_wg, t0 = 64, 5_000_000
+    rec = np.zeros((n_wg, 5), dtype=np.uint64)
+    for wg in range(n_wg):
+        x, local = wg % 8, wg // 8              # 8 workgroups per XCD: 4 slots, 2 rounds
+        dur = 100 + 10 * x
+        start = (local // 4) * dur
+        cu = (local % 4) // 2
+        rec[wg] = [t0 + 100 * start, t0 + 100 * (start + 3), t0 + 100 * (start + dur - 2), t0 + 100 * (start + dur),
+                   cu << 8]                       # counter ticks of 10 ns; hardware id: compute unit in bits 8-11
+
+    class FakeLib:
+        @staticmethod
+        def scalekv_timeline_read(dst, n):
+            ctypes.memmove(dst, rec.ctypes.data, rec.nbytes)
+            return 0
+
+    class FakeBinding:
+        @staticmethod
+        def lib():
+            return FakeLib
+
+    s = bench.timeline_summary(FakeBinding, n_wg)
+    assert s["workgroups"] == 64 and s["compute_units"] == 16
+    assert s["span_us"] == 340.0                                   # XCD 7: two rounds of 170 us
+    assert [p["last_end_us"] for p in s["per_xcd"]] == [200.0 + 20 * x for x in range(8)]
+    assert [p["mean_wg_us"] for p in s["per_xcd"]] == [100.0 + 10 * x for x in range(8)]
+    assert s["start_to_first_tile_us"] == 3.0 and s["loop_end_to_end_us"] == 2.0
+    assert abs(s["idle_at_the_end"] - (1 - 270.0 / 340.0)) < 1e-3  # mean end over the XCDs is 270 us
