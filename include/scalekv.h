@@ -3,13 +3,13 @@
  * AMD MI355X (gfx950).
  *
  * One call of scalekv_step does, for every (sequence, head) unit independently,
- * what Sec. 3.3 ("KV Cache Selection") of the paper describes for one layer at
+ * what the cache-selection paragraph of Sec. 3.3 of the paper describes for one layer at
  * one scale:
  *   1. score    importance of every cached token = attention mass it receives
  *               from the observation-window queries of the current token map
  *               (Eq. 5);
- *   2. select   the top-k cached tokens under the layer's budget (Sec. 3.3,
- *               "select the top-k^l tokens"; budgets come from Eq. 4);
+ *   2. select   the top-k cached tokens under the layer's budget (Sec. 3.3:
+ *               the k^l highest scores of layer l; budgets come from Eq. 4);
  *   3. compact  keep the selected K/V rows, drop the rest, append the current
  *               map's K/V (Sec. 3.3, last sentence of the selection paragraph);
  *   4. attend   the current map's queries attend, unmasked, over the kept rows
@@ -169,8 +169,8 @@ scalekv_status scalekv_step_static(const scalekv_shape* shape, const void* q, co
 /* ---- Sec. 3.3 read literally: the map's K/V join the cache, the map attends, and only
  * then is the cache pruned, with the observation window preserved. ---- */
 
-/* Observation window of Sec. 3.3 ("partition the map into N patches and select the
- * centroid token from each patch").  Host only, no GPU work.  The map has map_h rows and
+/* Observation window of Sec. 3.3: the map is cut into N patches and the token at the
+ * centre of each patch is taken.  Host only, no GPU work.  The map has map_h rows and
  * map_w columns in raster order and is cut into a grid of gr x gc patches, gr =
  * min(patch_rows, map_h), gc = min(patch_cols, map_w); band a of the rows covers rows
  * [floor(a*map_h/gr), floor((a+1)*map_h/gr)), likewise the columns.  The centroid of a
@@ -182,8 +182,8 @@ scalekv_status scalekv_window_centroids(int32_t map_h, int32_t map_w, int32_t pa
                                         int32_t patch_cols, int32_t* idx_out, int32_t* n_out);
 
 /* Selection of Sec. 3.3 with its two optional parts: average pooling of the scores
- * ("we aggregate these scores through average pooling") and preserved positions ("these
- * selected tokens, along with the observation window tokens, are preserved").
+ * (the aggregation step of the selection paragraph) and positions that are preserved whatever
+ * their score (the observation-window tokens, kept together with the selected ones).
  *   log_scores [S,H,cache_len] fp32 device: log of the importance scores (scalekv_score).
  *   pool_w: odd, 1..SCALEKV_MAX_POOL.  The scores are averaged along the cache axis over
  *     pool_w positions centred on each token, zeros beyond both ends, before ranking
@@ -282,7 +282,7 @@ scalekv_status scalekv_policy_table(const double* asi, int32_t n_layer, int32_t 
                                     int32_t* is_drafter, int32_t* b_r, int32_t* b_d,
                                     int64_t* slack);
 
-/* ---- Comparison policies of Sec. 4.1 ("Compression Baselines"), as index / budget
+/* ---- Comparison policies of Sec. 4.1 (its paragraph on compression baselines), as index / budget
  * generators for the same compact and attend calls; each is built from the one line the
  * paper gives it. ---- */
 

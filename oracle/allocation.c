@@ -2,8 +2,8 @@
  * ScaleKV oracle, the offline policy that feeds the per-step budget: the
  * Attention Selectivity Index (Eq. 2), its per-scale Z-score and the drafter
  * set (Eq. 3), the budget allocation (Eq. 4), and the index / budget rules of
- * the comparison policies the paper lists in Sec. 4.1 ("Compression
- * Baselines"), each taken from its one-line description there.
+ * the comparison policies the paper lists in Sec. 4.1 (its paragraph on
+ * compression baselines), each taken from its one-line description there.
  *
  * THIS IS TEST INFRASTRUCTURE, like scalekv_oracle.c beside it: plain fp64 /
  * integer loops, no code shared with the HIP library.
@@ -20,8 +20,9 @@
  *   cur_ratio[i]  = sum_{j in C_k} alpha_ij          (current attention ratio)
  *   hist_topk[i]  = sum of the top_k largest alpha_ij, j in P_{k-1}
  *                   (history top-K ratio; all of them if hist_len < top_k).
- * (The printed equation lost the summation range of its first factor; "the
- * proportion of attention directed to current token map" fixes it.)
+ * (The printed equation lost the summation range of its first factor; the text
+ * beside it says the factor is the share of attention that goes to the current
+ * map, which fixes the range.)
  * q: [n_s][d] sampled queries of the current map, k: [hist_len + cur_len][d].
  */
 void scalekv_oracle_asi_terms(const double* q, int n_s, const double* k, int hist_len, int cur_len,
@@ -81,8 +82,8 @@ double scalekv_oracle_asi(const double* cur_ratio, const double* hist_topk, int 
 
 /* -------------------------------------------------------------- Z-score --
  * Eq. 3: Z(l,k) = (ASI(l,k) - mu_k) / (sigma_k + eps), mu_k and sigma_k the mean
- * and standard deviation of ASI over the L layers at scale k ("we normalize
- * these values within each scale").  sigma_k is the population deviation
+ * and standard deviation of ASI over the L layers at scale k (the text says the
+ * normalisation is done inside each scale).  sigma_k is the population deviation
  * (divisor L); the paper does not say which.  asi, z: [L][K] row-major.
  */
 void scalekv_oracle_zscores(const double* asi, int L, int K, double eps, double* z) {
@@ -162,10 +163,10 @@ int scalekv_oracle_budgets(int L, int K, const int32_t* n_d, long long b_uniform
 
 /* ------------------------------------------------- comparison policies --
  * Sec. 4.1 lists them in one line each.  What is built from that line:
- *   sliding window  "retains local window of most recent tokens":
+ *   sliding window  (keeps a local window of the newest tokens):
  *                   the last n_recent positions;
- *   sinks + recent  "keeps attention sinks (initial tokens) and recent tokens":
- *                   the first n_sink positions and the last n_recent.
+ *   sinks + recent  (keeps the initial tokens, the attention sinks, and the
+ *                   newest tokens): the first n_sink positions and the last n_recent.
  * Both are the same rule (n_sink = 0 for the first).  If the two ranges meet,
  * every position is kept once.  idx receives the positions ascending; returns
  * their number, min(len, n_sink + n_recent).
@@ -177,8 +178,8 @@ int scalekv_oracle_positional(int len, int n_sink, int n_recent, int32_t* idx) {
   return t;
 }
 
-/* pyramid allocation "employs a fixed pyramid-shaped allocation strategy across
- * transformer layers": the per-layer budget falls linearly from the first layer
+/* pyramid allocation (a fixed, pyramid-shaped split of the budget over the
+ * layers): the per-layer budget falls linearly from the first layer
  * to the last while the mean stays b_uniform.  b_last (<= b_uniform) is the last
  * layer's budget, the first layer gets 2 b_uniform - b_last; for the lower half
  * l < L/2:  B(l) = b_first - floor((b_first - b_last) * l / (L - 1)), the upper

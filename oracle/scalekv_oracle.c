@@ -9,14 +9,15 @@
  * library.
  *
  * Everything is per (sequence, head) "unit": the method treats each head of
- * each sequence independently (Sec. 3.3, "for each attention head h").  The
+ * each sequence independently (Sec. 3.3 states its selection per attention
+ * head).  The
  * *_batch entry points only loop that per-unit code over units with OpenMP.
  *
  * Layouts: row-major doubles.  Q/K/V rows are tokens, columns are the
  * head_dim channels.
  *
  * The method is a heuristic eviction, so the functions below follow its steps
- * in the paper's order (Sec. 3.3, "KV Cache Selection"):
+ * in the paper's order (Sec. 3.3, the paragraph on cache selection):
  *   importance score (Eq. 5)  ->  top-k under the layer budget  ->  keep the
  *   selected rows, drop the rest  ->  the current map attends over what is
  *   kept plus its own K/V (Sec. 3.1: all tokens of a scale are produced in
@@ -98,8 +99,8 @@ void scalekv_oracle_score(const double* qw, int n_win, const double* k, int len,
 }
 
 /* --------------------------------------------------------------- select --
- * "select the top-k^l tokens with the highest aggregated importance scores"
- * (Sec. 3.3).  keep = min(budget, len).  Order tokens by score descending,
+ * Sec. 3.3: layer l keeps the k^l tokens whose aggregated importance score is
+ * highest.  keep = min(budget, len).  Order tokens by score descending,
  * equal scores by index ascending; take the first `keep`; report them in
  * ascending index order.  Written as `keep` rounds of a linear arg-max so
  * that nothing but the definition is involved.  Returns keep.
@@ -124,8 +125,8 @@ int scalekv_oracle_select(const double* score, int len, int budget, int32_t* idx
 }
 
 /* -------------------------------------------------------------- compact --
- * "Only the KV states of these selected tokens ... are preserved in the
- * cache for subsequent steps, while all others are ... pruned" (Sec. 3.3):
+ * Sec. 3.3: the K/V rows of the selected tokens stay in the cache for the later
+ * steps, every other row is dropped:
  *   dst[t] = src[idx[t]] for t < keep, then the current map's rows follow,
  *   dst[keep + t] = cur[t] for t < n_cur.  Returns the new length.
  */
@@ -177,8 +178,8 @@ void scalekv_oracle_attend(const double* q, int n_q, const double* k, const doub
  * indices; out receives n_cur rows.  budget >= cache_len keeps every row
  * (then the result is plain attention over the whole cache and the current
  * map).
- * The ranking of Sec. 3.3 ("the top-k^l tokens with the highest aggregated
- * importance scores") only depends on the order of the scores, and log is
+ * The ranking of Sec. 3.3 (the k^l highest aggregated scores) only depends on
+ * the order of the scores, and log is
  * strictly increasing, so the selection is taken on log s_i: the same order
  * wherever s_i is representable, and still an order where s_i itself would
  * underflow to zero (sharply peaked rows), where ranking on s_i would see a

@@ -1,6 +1,6 @@
 /*
- * ScaleKV oracle, second reading of Sec. 3.3 ("KV Cache Selection") taken
- * literally: the token map's K/V join the cache first, the map attends over
+ * ScaleKV oracle, second reading of Sec. 3.3 (its paragraph on cache selection)
+ * taken literally: the token map's K/V join the cache first, the map attends over
  * history and itself, and only then is the cache pruned, with the observation
  * window force-kept.
  *
@@ -16,9 +16,9 @@
  *      K holds every key the map sees (history and the map itself), so each
  *      window row is normalised over all of them;
  *   3. the scores are aggregated by average pooling;
- *   4. per layer the top-k^l tokens are selected, and "only the KV states of
- *      these selected tokens, along with the observation window tokens, are
- *      preserved ... for subsequent steps".
+ *   4. per layer the top-k^l tokens are selected; their K/V rows and those of
+ *      the observation-window tokens are what stays in the cache for the later
+ *      steps.
  * Where the paper leaves a detail open the choice made here is stated at the
  * function.
  */
@@ -33,8 +33,8 @@ void scalekv_oracle_attend(const double* q, int n_q, const double* k, const doub
                            int d, double scale, double* out);
 
 /* ------------------------------------------------------ window centroids --
- * "partition the map into N patches and select the centroid token from each
- * patch" (Sec. 3.3).  The map has h rows and w columns in raster order.  It is
+ * Sec. 3.3: the map is cut into N patches and the token at the centre of each
+ * patch is taken.  The map has h rows and w columns in raster order.  It is
  * cut into a grid of PH x PW patches, PH = min(ph, h), PW = min(pw, w) (a map
  * smaller than the grid gives one token per patch); band a of the rows covers
  * rows [floor(a*h/PH), floor((a+1)*h/PH)), likewise the columns.  The centroid
@@ -71,7 +71,7 @@ int scalekv_oracle_window_centroids(int h, int w, int ph, int pw, int32_t* idx) 
 }
 
 /* -------------------------------------------------------------- pooling --
- * "we aggregate these scores through average pooling" (Sec. 3.3).  Kernel
+ * Sec. 3.3 aggregates the scores by average pooling.  Kernel
  * size and padding are not given; taken as a 1-D average along the cache
  * axis, odd width pool_w, stride 1, zeros beyond both ends, divisor pool_w:
  *   out_i = (1/pool_w) * sum_{|t| <= (pool_w-1)/2} s_{i+t}.
