@@ -26,7 +26,7 @@ def test_centroids_of_odd_patches_are_the_exact_middles():
 
 
 def test_centroids_typical_window_is_16_tokens_and_even_patches_take_the_upper_left_middle():
-    # Sec. 3.3: the window "typically" has 16 tokens -> a 4 x 4 grid.  On the 64 x 64 map the
+    # Sec. 3.3: the window typically has 16 tokens -> a 4 x 4 grid.  On the 64 x 64 map the
     # patches are 16 x 16 and four tokens are equally central; the stated rule takes row 7, col 7.
     got = oracle.window_centroids(64, 64, 4, 4)
     assert len(got) == 16

@@ -43,7 +43,7 @@ class WorkloadConfig:
     head_dim: int
     prefix: int                # text-prefix tokens already cached before scale 1
     sides: Tuple[int, ...]     # side length of each scale's square token map
-    window: int                # observation-window size N (Sec. 3.3; "typically 16")
+    window: int                # observation-window size N (Sec. 3.3: typically 16)
     recipe: str                # value distribution, see generator.py
     n_drafter: int             # drafter layers per scale
     drafter_frac: float = 0.0  # budget as a fraction of the uncompressed cache length
