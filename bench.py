@@ -286,15 +286,15 @@ def attend_alone(args, torch, skv) -> int:
 
 def timeline_summary(skv, n_wg: int) -> dict:
     """Per-workgroup records of the last attention launch, from a library built with
-    `--variant timeline` (four readings of the 100 MHz counter and the hardware id register per
-    workgroup), summed up per XCD: hardware hands workgroup i to XCD i mod 8."""
+    `--variant timeline` (four readings of the 100 MHz counter, the hardware id register and two readings of
+    the shader clock counter per workgroup), summed up per XCD: hardware hands workgroup i to XCD i mod 8."""
     import ctypes
 
     import numpy as np
     L = skv.lib()
     if not hasattr(L, "scalekv_timeline_read"):
         raise SystemExit("--timeline needs --library <a build made with --variant timeline>")
-    rec = np.zeros((n_wg, 5), dtype=np.uint64)
+    rec = np.zeros((n_wg, 7), dtype=np.uint64)
     rc = L.scalekv_timeline_read(rec.ctypes.data_as(ctypes.c_void_p), ctypes.c_int(n_wg))
     if rc != 0:
         raise SystemExit(f"scalekv_timeline_read returned {rc}")
@@ -305,8 +305,11 @@ def timeline_summary(skv, n_wg: int) -> dict:
     span = float(t[:, 3].max())
     dur = t[:, 3] - t[:, 0]
     n_cu = sum(len(np.unique(cu[xcd == x])) for x in range(8))
+    cyc = (rec[:, 6] - rec[:, 5]).astype(np.float64)  # shader clock counter over the workgroup's life
     per_xcd = [{"xcd": x, "workgroups": int((xcd == x).sum()), "mean_wg_us": round(float(dur[xcd == x].mean()), 1),
-                "last_end_us": round(float(t[xcd == x, 3].max()), 1)} for x in range(8) if (xcd == x).any()]
+                "last_end_us": round(float(t[xcd == x, 3].max()), 1),
+                "clock_counter_mhz": round(float(cyc[xcd == x].sum() / dur[xcd == x].sum()), 1)}
+               for x in range(8) if (xcd == x).any()]
     ends = [p["last_end_us"] for p in per_xcd]
     return {"workgroups": n_wg, "compute_units": n_cu, "span_us": round(span, 1),
             "wg_us": {"mean": round(float(dur.mean()), 1), "min": round(float(dur.min()), 1), "max": round(float(dur.max()), 1)},

@@ -101,7 +101,7 @@ constexpr int kLdsBytes = 2 * kStages * kTileBytes;  // K stages then V stages: 
 #endif
 #if defined(SCALEKV_TIMELINE)
 constexpr int kTimelineMaxWg = 8192;
-constexpr int kTimelineWords = 5;  // four readings of the 100 MHz counter, then the hardware id register
+constexpr int kTimelineWords = 7;  // four readings of the 100 MHz counter, the hardware id register, the shader clock counter at start and end
 __device__ unsigned long long g_timeline[kTimelineMaxWg * kTimelineWords];
 #define SCALEKV_STAMP(name) const unsigned long long name = __builtin_amdgcn_s_memrealtime()
 #else
@@ -179,6 +179,7 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
   SCALEKV_STAMP(t_start);
 #if defined(SCALEKV_TIMELINE)
   unsigned long long t_first_tile = 0;
+  const unsigned long long c_start = __builtin_readcyclecounter();
 #endif
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* const k_lds = smem;
@@ -570,6 +571,8 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
     rec[2] = t_loop_end;
     rec[3] = __builtin_amdgcn_s_memrealtime();
     rec[4] = __builtin_amdgcn_s_getreg((31 << 11) | 4);  // HW_ID: compute unit, shader array, shader engine
+    rec[5] = c_start;
+    rec[6] = __builtin_readcyclecounter();
   }
 #endif
 }

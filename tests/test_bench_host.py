@@ -61,14 +61,14 @@ def test_timeline_summary_reads_per_xcd_times_from_the_records():
     import numpy as np
     bench = _bench_module()
     n_wg, t0 = 64, 5_000_000
-    rec = np.zeros((n_wg, 5), dtype=np.uint64)
+    rec = np.zeros((n_wg, 7), dtype=np.uint64)
     for wg in range(n_wg):
         x, local = wg % 8, wg // 8              # 8 workgroups per XCD: 4 slots, 2 rounds
         dur = 100 + 10 * x
         start = (local // 4) * dur
         cu = (local % 4) // 2
         rec[wg] = [t0 + 100 * start, t0 + 100 * (start + 3), t0 + 100 * (start + dur - 2), t0 + 100 * (start + dur),
-                   cu << 8]                       # counter ticks of 10 ns; hardware id: compute unit in bits 8-11
+                   cu << 8, 1000, 1000 + 2000 * dur]  # 10 ns ticks; compute unit in bits 8-11; a 2000 MHz clock counter
 
     class FakeLib:
         @staticmethod
@@ -86,5 +86,6 @@ def test_timeline_summary_reads_per_xcd_times_from_the_records():
     assert s["span_us"] == 340.0                                   # XCD 7: two rounds of 170 us
     assert [p["last_end_us"] for p in s["per_xcd"]] == [200.0 + 20 * x for x in range(8)]
     assert [p["mean_wg_us"] for p in s["per_xcd"]] == [100.0 + 10 * x for x in range(8)]
+    assert [p["clock_counter_mhz"] for p in s["per_xcd"]] == [2000.0] * 8
     assert s["start_to_first_tile_us"] == 3.0 and s["loop_end_to_end_us"] == 2.0
     assert abs(s["idle_at_the_end"] - (1 - 270.0 / 340.0)) < 1e-3  # mean end over the XCDs is 270 us
