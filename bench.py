@@ -284,6 +284,32 @@ def attend_alone(args, torch, skv) -> int:
     return 0
 
 
+def attend_clock_leg():
+    """The clock the chip holds under the attention kernel, per XCD: a child process runs
+    `--attend-alone 4096,5718 --timeline` with the measurement build of the library whose
+    workgroups read the shader clock counter (python -m paper_2505_19602_amd.build --variant
+    timeline); None if that build is not there.  Outside the timed region."""
+    import subprocess
+    lib = os.path.join(ROOT, "paper_2505_19602_amd", "libscalekv_timeline.so")
+    if not os.path.exists(lib):
+        return None
+    cmd = [sys.executable, os.path.abspath(__file__), "--attend-alone", "4096,5718", "--reps", "5", "--timeline",
+           "--library", lib]
+    try:
+        res = subprocess.run(cmd, capture_output=True, text=True, timeout=180, cwd=ROOT)
+        line = json.loads(res.stdout.strip().splitlines()[-1])
+        mhz = [x["clock_counter_mhz"] for x in line["timeline"]["per_xcd"]]
+        mean = sum(mhz) / len(mhz)
+        peak = PEAK_BF16_TFLOPS * mean / 2400.0
+        return {"shape": "attention kernel alone, 4096 queries x 5718 keys x 256 units", "tflops": line["tflops"],
+                "mhz_per_xcd": mhz, "mhz_mean": mean, "matrix_peak_at_that_clock_tflops": peak,
+                "frac_of_that_peak": line["tflops"] / peak, "idle_at_the_end": line["timeline"]["idle_at_the_end"],
+                "note": "shader clock counter over 100 MHz counter, summed over each XCD's workgroups; the vendor peak "
+                        "assumes 2400 MHz; idle_at_the_end = share of the launch the XCDs, on average, wait for the slowest"}
+    except Exception as exc:
+        return {"error": f"{type(exc).__name__}: {exc}"[:300]}
+
+
 def timeline_summary(skv, n_wg: int) -> dict:
     """Per-workgroup records of the last attention launch, from a library built with
     `--variant timeline` (four readings of the 100 MHz counter, the hardware id register and two readings of
@@ -398,6 +424,8 @@ def main() -> int:
     ap.add_argument("--pool-w", type=int, default=7, help="score pooling width of --variant literal")
     ap.add_argument("--shared-inputs", action="store_true",
                     help="reuse layer 0's Q/K/V in every layer (less memory, faster set-up)")
+    ap.add_argument("--no-clock-leg", action="store_true",
+                    help="skip the child run that reads the clock the attention kernel runs at (needs the timeline build)")
     ap.add_argument("--no-parity", action="store_true",
                     help="skip the replay of sampled last-scale units through the CPU oracle after the timed region")
     ap.add_argument("--cases", default=None,
@@ -833,6 +861,7 @@ def main() -> int:
         "standalone_kernels": standalone,
         "calibration": calibration,
         "hip_graph_replay": None,
+        "attend_clock": None,
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS,
                         "last_scale": gbs(compact_last), "last_scale_frac": gbs(compact_last) / PEAK_HBM_GBS,
@@ -918,6 +947,9 @@ def main() -> int:
         except Exception as exc:   # the eager numbers above stand on their own
             result["hip_graph_replay"] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
             log(f"graph replay failed: {exc}")
+    if not args.no_clock_leg and variant == "scalekv":
+        result["attend_clock"] = attend_clock_leg()
+        log(f"attention kernel's clock: {result['attend_clock']}")
     if not args.no_cpu_baseline and variant == "scalekv":
         log("timing the CPU oracle on its sample ...")
         del inputs, bufs
