@@ -43,12 +43,15 @@
 // probabilities, the very numbers the MFMA multiplies by.  No running maximum is
 // formed (it costs a sixth of the vector instructions of a block).  This is exact as
 // long as nothing overflows, and fp32 / bf16 carry 2^127: a lane only checks that its
-// share of a block's row sum stays below 2^40 and records a failure in a scalar mask.
-// If any wave of the workgroup recorded one (scores more than 27 natural units above
-// the first tile's maximum: not seen with attention-like inputs, forced by the tests),
-// the workgroup discards its result and repeats the whole pass with the classical
-// scheme: running maximum per block, offsets moved (and O, l rescaled) when some row
-// maximum grew by more than kRescaleThreshold in log2 units.
+// share of a block's row sum stays below 2^100 (scores up to 69 natural units above the
+// first tile's maximum: heavy-tailed keys reach 35) and records a failure in a scalar
+// mask; row sums then stay below 2^114.  The accumulators could still overflow if the
+// values themselves are huge (2^100 times 2^14 keys leaves room for |v| up to 2^13), so
+// at the end of the pass every lane also checks that its accumulators are finite.
+// If any wave of the workgroup recorded a failure (forced by the tests), the workgroup
+// discards its result and repeats the whole pass with the classical scheme: running
+// maximum per block, offsets moved (and O, l rescaled) when some row maximum grew by
+// more than kRescaleThreshold in log2 units.
 //
 // Workgroups of one (sequence, head) unit are numbered so that they land on the
 // same XCD and share its L2 while they stream the same K/V.
@@ -107,7 +110,7 @@ __device__ unsigned long long g_timeline[kTimelineMaxWg * kTimelineWords];
 #else
 #define SCALEKV_STAMP(name)
 #endif
-constexpr float kBlockSumLimit = 1099511627776.f;  // 2^40: largest row-sum share a block may add unchecked
+constexpr float kBlockSumLimit = 0x1p100f;  // largest row-sum share a block may add unchecked
 constexpr int kXcds = 8;
 
 // Three-input max as one instruction and without the NaN-quieting pre-pass the
@@ -468,6 +471,15 @@ void attend_pipe_kernel(const uint16_t* __restrict__ q, int n_q, uint16_t* k, lo
       tile(tracked, t + 1, 0, kTileBytes);
     }
     if (t < n_tile) tile(tracked, t, kTileBytes, 0);
+    if constexpr (!decltype(tracked)::value) {
+      // inf or NaN in an accumulator (huge values times large unchecked weights): repeat tracked
+      bool bad = false;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bad |= !(fabsf(o[db][r]) < INFINITY);
+      overflowed |= __builtin_amdgcn_ballot_w64(bad);
+    }
   };
   pass(std::false_type{}, std::true_type{});
   // every wave has left its last tile when the votes are in, so the stages may be refilled

@@ -157,19 +157,29 @@ def test_attend_matches_oracle(dtype, d, n_q, kv_len):
     _note(f"  max {mx:.2e} mean {mean:.2e}")
 
 
-@pytest.mark.parametrize("where", ["late_in_cache", "in_current_map", "second_tile", "some_rows_only"])
+@pytest.mark.parametrize("where", ["late_in_cache", "in_current_map", "second_tile", "some_rows_only",
+                                   "large_but_unchecked", "huge_values"])
 def test_attend_scores_far_above_the_first_tile(where):
     # Keys whose scores sit far above everything in the first 64 rows: exp2 of their distance to
-    # the first tile's maximum leaves the range the kernel adds up unchecked (and, for the larger
+    # the first tile's maximum leaves the range the kernel adds up unchecked (2^100; for the larger
     # gaps, fp32 altogether), so the workgroup has to fall back to the running-maximum scheme.
+    # "large_but_unchecked": a gap of about 34 natural units (2^49), which the kernel adds up as it
+    # is; "huge_values": the same gap with value rows of magnitude 2^100, whose weighted sums leave
+    # fp32 although the weights do not, so the accumulators' own check has to trigger.
     S, H, d, n_q, len1, len2 = 1, 2, 128, 300, 400, 300
     dtype = torch.bfloat16
     _note(f"attend overflow fallback: {where}")
     shape = skv.Shape(S, H, d, dtype)
     q = _rand(40, (S, H, n_q, d), dtype)
     ks, vs = _rand(41, (S, H, len1 + len2, d), dtype, 0.05), _rand(42, (S, H, len1 + len2, d), dtype)
-    row = {"late_in_cache": len1 - 3, "in_current_map": len1 + 170, "second_tile": 70, "some_rows_only": 333}[where]
-    gain = {"late_in_cache": 8.0, "in_current_map": 30.0, "second_tile": 3.0, "some_rows_only": 6.0}[where]
+    row = {"late_in_cache": len1 - 3, "in_current_map": len1 + 170, "second_tile": 70, "some_rows_only": 333,
+           "large_but_unchecked": 200, "huge_values": 200}[where]
+    gain = {"late_in_cache": 9.0, "in_current_map": 30.0, "second_tile": 10.0, "some_rows_only": 10.0,
+            "large_but_unchecked": 3.0, "huge_values": 3.0}[where]
+    post = 1.0
+    if where == "huge_values":
+        vs = (vs.float() * 2.0 ** 100).to(dtype)
+        post = 2.0 ** -100           # outputs are compared after this exact rescaling
     if where == "some_rows_only":       # only queries 5..9 see the large scores
         ks[:, :, row] = (q[:, :, 5].float() * gain).to(dtype)
         q[:, :, 6:10] = q[:, :, 5:6]
@@ -180,8 +190,8 @@ def test_attend_scores_far_above_the_first_tile(where):
     out = torch.full((S, H, n_q, d), float("nan"), dtype=dtype, device=DEV)
     skv.attend(shape, q.to(DEV), ks.to(DEV), vs.to(DEV), len1 + len2, out)       # one segment
     torch.cuda.synchronize()
-    ref = oracle.attend(units(q), units(ks), units(vs))
-    check_output(out, ref, dtype, f"attend {where}")
+    ref = oracle.attend(units(q), units(ks), units(vs)) * post
+    check_output(out.float() * post, ref, dtype, f"attend {where}")
     # the same keys as cache + current map through the step (budget = len1 keeps every cached row):
     # two key segments, and the kernel appends the map's K/V itself
     kd = torch.zeros(S, H, len1 + len2 + 2, d, dtype=dtype, device=DEV); vd = torch.zeros_like(kd)
@@ -192,7 +202,7 @@ def test_attend_scores_far_above_the_first_tile(where):
     assert new_len == len1 + len2
     assert torch.equal(kd[:, :, :new_len].cpu(), ks) and torch.equal(vd[:, :, :new_len].cpu(), vs)
     assert torch.all(kd[:, :, new_len:] == 0) and torch.all(vd[:, :, new_len:] == 0)
-    check_output(out2, ref, dtype, f"step {where}")
+    check_output(out2.float() * post, ref, dtype, f"step {where}")
 
 
 def test_attend_closed_forms_on_gpu():
