@@ -510,6 +510,70 @@ def test_step_sweep_of_sizes_around_the_tile_edges():
         check_output(out, ref["out"], dtype, f"sweep case {case}")
 
 
+def test_step_random_shapes_follow_the_oracle():
+    """Seeded whole steps at sizes drawn at random rather than at tile edges (maps of 1-700 tokens,
+    caches of 0-2500 rows, budgets from 0 to beyond the cache, windows in any order, three logit
+    scales, both dtypes and head sizes), with canary rows behind the new cache; every unit is
+    followed by the oracle."""
+    rng = np.random.default_rng(20251128)
+    for case in range(60):
+        dtype = torch.bfloat16 if rng.random() < 0.8 else torch.float32
+        d = 128 if rng.random() < 0.7 else 64
+        S, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        n_cur = int(rng.choice([rng.integers(1, 40), rng.integers(1, 200), rng.integers(100, 700)]))
+        L = int(rng.choice([rng.integers(0, 40), rng.integers(0, 600), rng.integers(300, 2500)]))
+        budget = int(rng.choice([0, 1, rng.integers(0, L + 2), rng.integers(0, L + 2), max(0, L - 1), L, L + 3]))
+        keep = min(budget, L)
+        n_win = int(rng.integers(1, min(16, n_cur) + 1))
+        win = [int(x) for x in rng.choice(n_cur, size=n_win, replace=False)]
+        logit_scale = float(rng.choice([0.3, 1.0, 2.5]))
+        pad = int(rng.integers(0, 4))
+        _note(f"random step case={case} dtype={dtype} d={d} S={S} H={H} n_cur={n_cur} L={L} budget={budget} "
+              f"n_win={n_win} scale={logit_scale} pad={pad}")
+        shape = skv.Shape(S, H, d, dtype)
+        q, kc, vc = (_rand(5000 + 7 * case + i, (S, H, n_cur, d), dtype, logit_scale if i < 2 else 1.0) for i in range(3))
+        ks = _rand(5000 + 7 * case + 3, (S, H, max(L, 1), d), dtype, logit_scale)
+        vs = _rand(5000 + 7 * case + 4, (S, H, max(L, 1), d), dtype)
+        ws = torch.empty(skv.workspace_bytes(shape, max(L, 1), n_cur), dtype=torch.uint8, device=DEV)
+        kd = torch.full((S, H, keep + n_cur + pad, d), 3.0, dtype=dtype, device=DEV); vd = torch.full_like(kd, 3.0)
+        out = torch.full((S, H, n_cur, d), float("nan"), dtype=dtype, device=DEV)
+        idx = torch.full((S, H, keep), -1, dtype=torch.int32, device=DEV)
+        new_len = skv.step(shape, q.to(DEV), kc.to(DEV), vc.to(DEV), win, ks.to(DEV), vs.to(DEV), L, budget,
+                           kd, vd, out, idx, ws)
+        torch.cuda.synchronize()
+        assert new_len == keep + n_cur
+        assert torch.all(kd[:, :, new_len:] == 3.0) and torch.all(vd[:, :, new_len:] == 3.0)
+        g_idx = idx.cpu().numpy().reshape(S * H, keep)
+        k_u, v_u = units(ks)[:, :L], units(vs)[:, :L]
+        own = oracle.step(units(q), units(kc), units(vc), win, k_u, v_u, budget)
+        for u in range(S * H):
+            check_indices(g_idx[u], own["log_scores"][u], keep, own["idx"][u])
+        ref = oracle.step(units(q), units(kc), units(vc), win, k_u, v_u, budget, force_idx=g_idx)
+        assert np.array_equal(units(kd)[:, :new_len].double().numpy(), ref["k_dst"])
+        assert np.array_equal(units(vd)[:, :new_len].double().numpy(), ref["v_dst"])
+        check_output(out, ref["out"], dtype, f"random step case {case}")
+
+
+def test_attend_heavy_tailed_keys_at_random_shapes():
+    """The pipelined attention kernel on Student-t keys scaled by 1 to 10: rows whose later scores
+    sit a little, far, or too far above the first tile's maximum, so that workgroups with and
+    without the repeat pass (and both kinds in one launch) are compared with the oracle."""
+    rng = np.random.default_rng(20251129)
+    dtype, d = torch.bfloat16, 128
+    for case in range(24):
+        S, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        n_q, kv = int(rng.integers(129, 700)), int(rng.integers(65, 3000))
+        scale = float(rng.choice([1.0, 3.0, 6.0, 10.0]))
+        _note(f"heavy-tailed attend case={case} S={S} H={H} n_q={n_q} kv={kv} scale={scale}")
+        q = _rand(7000 + 3 * case, (S, H, n_q, d), dtype)
+        k = (W.student_t_tensor(W.stream_key(7001, case), W.stream_key(7002, case), (S, H, kv, d)) * scale).to(dtype)
+        v = _rand(7000 + 3 * case + 2, (S, H, kv, d), dtype)
+        out = torch.full((S, H, n_q, d), float("nan"), dtype=dtype, device=DEV)
+        skv.attend(skv.Shape(S, H, d, dtype), q.to(DEV), k.to(DEV), v.to(DEV), kv, out)
+        torch.cuda.synchronize()
+        check_output(out, oracle.attend(units(q), units(k), units(v)), dtype, f"heavy-tailed attend case {case}")
+
+
 def test_step_one_hot_pattern_selects_its_argmax():
     dtype, S, H, d, L, n_cur = torch.bfloat16, 1, 2, 128, 400, 32
     shape = skv.Shape(S, H, d, dtype)
