@@ -64,8 +64,11 @@ struct ScoreInputs {
 // streams the unit's cached keys itself (16 waves x 32 keys per round, logits to the workspace,
 // running row maximum and sum of exponentials per wave), so that neither a second launch nor the
 // per-chunk statistics are needed; then it ranks as in the FUSED form.
-template <bool IN_LDS, bool FUSED, int SCORE_D>
-__global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores,
+// MIN_WAVES = 8 holds the kernel to 64 registers so that two workgroups share a compute unit (one
+// streams keys while the other ranks): for launches with more units than compute units.  With
+// one workgroup per compute unit the unconstrained form (MIN_WAVES = 4) is a little faster.
+template <bool IN_LDS, bool FUSED, int SCORE_D, int MIN_WAVES = 4>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(MIN_WAVES, 8))) void select_kernel(const float* __restrict__ scores,
                                                           long long score_unit_stride,
                                                           int cache_len, int keep,
                                                           int32_t* __restrict__ idx,
@@ -321,7 +324,11 @@ hipError_t launch_score_select(int dtype, int n_seq, int n_head, int d, const vo
     si.k_cur = (const uint16_t*)prune->k_cur; si.v_cur = (const uint16_t*)prune->v_cur;
     si.n_app = prune->k_cur ? prune->n_app : 0;
   }
-  if (d == 128)
+  constexpr int kComputeUnits = 256;  // MI355X
+  if (d == 128 && n_unit > kComputeUnits)
+    hipLaunchKernelGGL((select_kernel<true, true, 128, 8>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
+                       0, cache_len, keep, idx, ws, n_win, ex, si);
+  else if (d == 128)
     hipLaunchKernelGGL((select_kernel<true, true, 128>), dim3(n_unit), dim3(kThreads), 0, stream, nullptr,
                        0, cache_len, keep, idx, ws, n_win, ex, si);
   else
