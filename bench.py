@@ -865,7 +865,7 @@ def main() -> int:
         "attend_tflops_all_scales": attend_all["flops"] / (attend_all["ms"] * 1e-3) / 1e12 if attend_all["ms"] else 0.0,
         "compact_hbm": {"achieved": compact_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": compact_gbs / PEAK_HBM_GBS,
                         "last_scale": gbs(compact_last), "last_scale_frac": gbs(compact_last) / PEAK_HBM_GBS,
-                        "kernel": "select_kernel<true, true, 128>: score + select + gather of the kept rows in one launch",
+                        "kernel": "select_kernel<true, true, 128, 4>: score + select + gather of the kept rows in one launch",
                         "note": "algorithmic bytes of the kernel that carries the compaction (keys read once for the "
                                 "score, kept K/V rows read and written) over its time in the instrumented pass, steps "
                                 "that rank only; its fp32 logits (64 B per key, mostly L2) are not counted; the map's "
