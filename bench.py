@@ -323,7 +323,8 @@ def timeline_summary(skv, n_wg: int) -> dict:
     rec = np.zeros((n_wg, 7), dtype=np.uint64)
     rc = L.scalekv_timeline_read(rec.ctypes.data_as(ctypes.c_void_p), ctypes.c_int(n_wg))
     if rc != 0:
-        raise SystemExit(f"scalekv_timeline_read returned {rc}")
+        raise SystemExit(f"scalekv_timeline_read returned {rc} (the build keeps records of at most 8192 workgroups; "
+                         f"this launch has {n_wg})")
     t = (rec[:, :4].astype(np.int64) - int(rec[:, 0].min())) * 0.01  # us since the first workgroup started
     hw = rec[:, 4].astype(np.int64)
     xcd = np.arange(n_wg) % 8
